@@ -1,0 +1,195 @@
+/*
+ * prism.h -- C ABI of libprism: one edge server's placement-aware MoE layer
+ * forward on one AMD MI355X (gfx950), as hand-written HIP kernels.
+ *
+ * Paper: "Prism" (arXiv 2508.12851), Sec. III-A (system architecture: each
+ * server's gating network picks experts "whether local or remote", local
+ * experts run, results are aggregated, gating decisions are logged for the
+ * global scheduler) and Sec. III-B (activation frequency f_n^l(e), placement
+ * z_{n,g}^e, indicator 1_remote(n,e), proxy objective Eq. 2).
+ *
+ * The paper fixes the roles of the steps, not their formulas; this library
+ * uses the standard top-k softmax gating and bias-free SwiGLU experts of the
+ * two model families the paper evaluates (Sec. IV):
+ *
+ *   logit[t,e] = fl32( sum_h x[t,h] * W_r[e,h] ) + bias[row(t), e]
+ *                (the sum is accumulated in fp64 and rounded once to fp32;
+ *                 the fp32 bias is added in fp32)
+ *   top-k      : k picks per token by descending logit, lowest expert index
+ *                wins ties; slot j holds the j-th pick
+ *   gate[t,j]  = exp(l_j - l_0) / sum_j' exp(l_j' - l_0)   (sums to 1)
+ *   counts[e]  = number of (t,j) with topk_idx[t,j] == e   (all experts,
+ *                hosted or not: the raw f_n^l(e))
+ *   local(a)   = local_mask[topk_idx[a]] != 0 for assignment a = t*k + j
+ *                (local_mask[e] = [sum_g z_{n,g}^e >= 1] = 1 - 1_remote(n,e))
+ *   y_a        = W_down^e ( silu(W_gate^e x_t) * (W_up^e x_t) ),
+ *                silu(z) = z / (1 + exp(-z))
+ *   out[t]     = sum_{j : local} gate[t,j] * y_(t,j) + sum_s y^shared_(s,t)
+ *                (the local partial sum; remote slots are only listed)
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless marked "host".  All matrices
+ *     are dense row-major.  The caller owns every buffer; the library
+ *     allocates nothing on the device and keeps no state between calls.
+ *   - Every call only enqueues work on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and never synchronises.  Values that
+ *     depend on routing (counts, n_local_remote, remote_bytes, offsets) stay
+ *     in device memory; the caller copies them back when it wants them.
+ *   - Errors are return codes only.  Arguments are validated on the host
+ *     before anything is launched: a NULL required pointer, T < 0, k < 1 or
+ *     k > E give PRISM_ERR_INVALID_ARG; sizes outside the compiled limits
+ *     give PRISM_ERR_UNSUPPORTED; a workspace smaller than
+ *     prism_workspace_bytes() gives PRISM_ERR_WORKSPACE_TOO_SMALL; a failed
+ *     kernel launch gives PRISM_ERR_LAUNCH.  T == 0 is PRISM_OK and writes
+ *     zero counts / offsets / totals.
+ *   - Inputs are assumed finite (not checked).
+ *   - Integer outputs are a pure function of the inputs (deterministic).
+ *
+ * Limits: 1 <= E <= 256, 1 <= k <= 8, k <= E, S <= 16, T*k + S*T < 2^30.
+ * H % 8 == 0 for both dtypes; PRISM_BF16 additionally needs H % 64 == 0 and
+ * F % 64 == 0 in the FFN, combine and whole-layer calls.  Weight and token
+ * matrices must be 16-byte aligned.
+ */
+#ifndef PRISM_H_
+#define PRISM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PRISM_OK = 0,
+  PRISM_ERR_INVALID_ARG = 1,
+  PRISM_ERR_UNSUPPORTED = 2,
+  PRISM_ERR_WORKSPACE_TOO_SMALL = 3,
+  PRISM_ERR_LAUNCH = 4
+} prism_status;
+
+typedef enum { PRISM_F32 = 0, PRISM_BF16 = 1 } prism_dtype;
+
+#define PRISM_MAX_EXPERTS 256
+#define PRISM_MAX_TOPK 8
+#define PRISM_MAX_SHARED 16
+
+/* Layer description: plain data in HOST memory, passed by const pointer. */
+typedef struct {
+  int32_t hidden;            /* H */
+  int32_t ffn;               /* F */
+  int32_t n_experts;         /* E routed experts */
+  int32_t top_k;             /* k */
+  int32_t n_shared;          /* S always-on shared experts (hosted everywhere) */
+  int32_t dtype;             /* prism_dtype of x, every weight matrix, y and out */
+  int32_t bias_group_tokens; /* 0: bias row 0 for all tokens; else row = t / this */
+} prism_layer_desc;
+
+/*
+ * Expert weights: a HOST struct holding DEVICE arrays of device pointers.
+ * w_gate[e], w_up[e] are [F,H]; w_down[e] is [H,F]; e in [0,E).  An entry may
+ * be NULL iff local_mask[e] == 0 (the expert is hosted elsewhere); a hosted
+ * expert with a NULL pointer is undefined behaviour.  The shared_* arrays
+ * have S entries and may be NULL when S == 0.
+ */
+typedef struct {
+  const void* const* w_gate;
+  const void* const* w_up;
+  const void* const* w_down;
+  const void* const* shared_w_gate;
+  const void* const* shared_w_up;
+  const void* const* shared_w_down;
+} prism_expert_weights;
+
+/* Static text for a status code (host pointer, never NULL). */
+const char* prism_status_string(prism_status s);
+
+/*
+ * Workspace size in bytes (written to the host variable *bytes) that any
+ * entry point below needs for a batch of up to max_tokens tokens of this
+ * layer.  The workspace must be 256-byte aligned; its contents between calls
+ * are irrelevant.
+ */
+prism_status prism_workspace_bytes(const prism_layer_desc* desc, int32_t max_tokens, size_t* bytes);
+
+/*
+ * Gating network + activation statistics (Sec. III-A gating network; Sec.
+ * III-B frequency f_n^l(e)).
+ *   x            [T,H] layer dtype
+ *   w_router     [E,H] layer dtype
+ *   router_bias  [G,E] fp32 or NULL; G = 1 or ceil(T / bias_group_tokens)
+ *   logits       [T,E] fp32 out, or NULL if not wanted
+ *   topk_idx     [T,k] int32 out
+ *   topk_gate    [T,k] fp32 out
+ *   counts       [E] int32 out, overwritten with this call's counts
+ *   counts_accum [E] int64, += this call's counts; or NULL
+ */
+prism_status prism_route(const prism_layer_desc* desc, const void* x, const void* w_router,
+                         const float* router_bias, int32_t T, float* logits, int32_t* topk_idx,
+                         float* topk_gate, int32_t* counts, int64_t* counts_accum, void* stream);
+
+/*
+ * Placement split (Sec. III-B, indicator 1_remote) and stable bucketing.
+ * Assignment a = t*k + j is local iff local_mask[topk_idx[a]] != 0.
+ *   local_src      [T*k] int32 out: the local assignments, bucketed by expert
+ *                  in ascending expert order, ascending a inside a bucket;
+ *                  entries past n_local are not written
+ *   local_offsets  [E+1] int32 out: bucket e is local_src[off[e] .. off[e+1])
+ *   remote_src / remote_offsets: the same for the assignments whose expert is
+ *                  not hosted here (the remote-dispatch list)
+ *   n_local_remote [2] int32 out: {n_local, n_remote}
+ *   remote_bytes   [2] int64 out: {bytes to send, bytes to receive} =
+ *                  n_remote * H * sizeof(element) each (one activation row per
+ *                  remote assignment each way, Sec. III-B "transmitting
+ *                  activations ... sending results back")
+ */
+prism_status prism_dispatch(const prism_layer_desc* desc, const int32_t* topk_idx,
+                            const uint8_t* local_mask, int32_t T, int32_t* local_src,
+                            int32_t* local_offsets, int32_t* remote_src, int32_t* remote_offsets,
+                            int32_t* n_local_remote, int64_t* remote_bytes, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/*
+ * Grouped SwiGLU FFN over the locally hosted experts and the shared experts
+ * (the local expert execution of Sec. III-A).
+ *   y  [T*k + S*T, H] layer dtype out: row r < n_local is the expert output
+ *      of assignment local_src[r] (token local_src[r] / k, expert = bucket of
+ *      r); rows n_local .. T*k-1 are not written; row T*k + s*T + t is
+ *      shared expert s applied to token t.
+ * bf16: products accumulate in fp32, silu*up is formed in fp32 and rounded to
+ * bf16 once before the down projection, y is rounded to bf16 once.
+ */
+prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
+                              const prism_expert_weights* weights, const int32_t* local_src,
+                              const int32_t* local_offsets, int32_t T, void* y, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/*
+ * Gate-weighted aggregation of the local expert outputs (Sec. III-A
+ * "aggregated"): out[t] = sum over local slots j (ascending) of
+ * topk_gate[t,j] * y[row of (t,j)], then + shared rows s = 0..S-1, in fp32,
+ * rounded once to the layer dtype.  A token with no local slot and S == 0
+ * gets zeros.
+ *   out [T,H] layer dtype
+ */
+prism_status prism_combine(const prism_layer_desc* desc, const void* y, const int32_t* local_src,
+                           const int32_t* local_offsets, const float* topk_gate, int32_t T,
+                           void* out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The whole layer: route -> dispatch -> expert FFN -> combine, on one stream,
+ * with no host synchronisation.  Outputs as in the calls above; local_src,
+ * local_offsets, the FFN intermediate and y live in the workspace.
+ */
+prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const void* w_router,
+                             const float* router_bias, const prism_expert_weights* weights,
+                             const uint8_t* local_mask, int32_t T, void* out, int32_t* topk_idx,
+                             float* topk_gate, int32_t* counts, int64_t* counts_accum,
+                             int32_t* remote_src, int32_t* remote_offsets,
+                             int32_t* n_local_remote, int64_t* remote_bytes, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRISM_H_ */

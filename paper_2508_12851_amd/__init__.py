@@ -1,0 +1,9 @@
+"""MI355X-native placement-aware MoE layer (one edge server's forward of the
+Prism system, arXiv 2508.12851): HIP kernels behind the C ABI of
+include/prism.h, plus a thin ctypes binding.  Importing this package does not
+load the library; the first call (or load_library()) does."""
+from .binding import (  # noqa: F401
+    ExpertWeights, LayerDesc, LayerOut, PrismError, WeightTable, alloc_layer_out, alloc_workspace,
+    load_library, make_desc, prism_combine, prism_dispatch, prism_expert_ffn, prism_moe_layer,
+    prism_route, torch_dtype, workspace_bytes, LIB_PATH, SYMBOLS,
+)

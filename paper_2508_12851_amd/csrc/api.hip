@@ -1,0 +1,163 @@
+// C ABI of libprism: host-side validation, workspace carving and launch order.
+#include "prism_internal.h"
+
+namespace prism {
+
+prism_status validate_desc(const prism_layer_desc* d, int32_t T, bool need_ffn_shapes) {
+  PRISM_RETURN_IF(d == nullptr, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(T < 0, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(d->hidden < 1 || d->n_experts < 1 || d->n_shared < 0, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(d->top_k < 1 || d->top_k > d->n_experts, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(d->bias_group_tokens < 0, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(d->dtype != PRISM_F32 && d->dtype != PRISM_BF16, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(d->n_experts > PRISM_MAX_EXPERTS || d->top_k > PRISM_MAX_TOPK ||
+                      d->n_shared > PRISM_MAX_SHARED,
+                  PRISM_ERR_UNSUPPORTED);
+  PRISM_RETURN_IF(d->hidden % 8 != 0, PRISM_ERR_UNSUPPORTED);
+  const long long rows = (long long)T * d->top_k + (long long)T * d->n_shared;
+  PRISM_RETURN_IF(rows >= (1LL << 30), PRISM_ERR_UNSUPPORTED);
+  if (need_ffn_shapes) {
+    PRISM_RETURN_IF(d->ffn < 1, PRISM_ERR_INVALID_ARG);
+    if (d->dtype == PRISM_BF16)
+      PRISM_RETURN_IF(d->hidden % 64 != 0 || d->ffn % 64 != 0, PRISM_ERR_UNSUPPORTED);
+  }
+  return PRISM_OK;
+}
+
+static prism_status check_workspace(const prism_layer_desc& d, int T, void* ws, size_t ws_bytes,
+                                    Workspace* out) {
+  PRISM_RETURN_IF(ws == nullptr, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(((uintptr_t)ws & 255u) != 0, PRISM_ERR_INVALID_ARG);
+  const Workspace probe = carve(d, T, nullptr);
+  PRISM_RETURN_IF(ws_bytes < probe.total, PRISM_ERR_WORKSPACE_TOO_SMALL);
+  *out = carve(d, T, ws);
+  return PRISM_OK;
+}
+
+static prism_status check_weights(const prism_layer_desc& d, const prism_expert_weights* w) {
+  PRISM_RETURN_IF(w == nullptr, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(w->w_gate == nullptr || w->w_up == nullptr || w->w_down == nullptr,
+                  PRISM_ERR_INVALID_ARG);
+  if (d.n_shared > 0)
+    PRISM_RETURN_IF(w->shared_w_gate == nullptr || w->shared_w_up == nullptr ||
+                        w->shared_w_down == nullptr,
+                    PRISM_ERR_INVALID_ARG);
+  return PRISM_OK;
+}
+
+}  // namespace prism
+
+using namespace prism;
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+const char* prism_status_string(prism_status s) {
+  switch (s) {
+    case PRISM_OK: return "ok";
+    case PRISM_ERR_INVALID_ARG: return "invalid argument";
+    case PRISM_ERR_UNSUPPORTED: return "size or dtype outside the supported limits";
+    case PRISM_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case PRISM_ERR_LAUNCH: return "kernel launch failed";
+  }
+  return "unknown status";
+}
+
+prism_status prism_workspace_bytes(const prism_layer_desc* desc, int32_t max_tokens, size_t* bytes) {
+  PRISM_RETURN_IF(bytes == nullptr, PRISM_ERR_INVALID_ARG);
+  PRISM_TRY(validate_desc(desc, max_tokens, true));
+  *bytes = carve(*desc, max_tokens, nullptr).total;
+  return PRISM_OK;
+}
+
+prism_status prism_route(const prism_layer_desc* desc, const void* x, const void* w_router,
+                         const float* router_bias, int32_t T, float* logits, int32_t* topk_idx,
+                         float* topk_gate, int32_t* counts, int64_t* counts_accum, void* stream) {
+  PRISM_TRY(validate_desc(desc, T, false));
+  PRISM_RETURN_IF(counts == nullptr, PRISM_ERR_INVALID_ARG);
+  if (T > 0)
+    PRISM_RETURN_IF(x == nullptr || w_router == nullptr || topk_idx == nullptr || topk_gate == nullptr,
+                    PRISM_ERR_INVALID_ARG);
+  return launch_route(*desc, x, w_router, router_bias, T, logits, topk_idx, topk_gate, counts,
+                      counts_accum, (hipStream_t)stream);
+}
+
+prism_status prism_dispatch(const prism_layer_desc* desc, const int32_t* topk_idx,
+                            const uint8_t* local_mask, int32_t T, int32_t* local_src,
+                            int32_t* local_offsets, int32_t* remote_src, int32_t* remote_offsets,
+                            int32_t* n_local_remote, int64_t* remote_bytes, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  PRISM_TRY(validate_desc(desc, T, false));
+  PRISM_RETURN_IF(local_mask == nullptr || local_offsets == nullptr || remote_offsets == nullptr ||
+                      n_local_remote == nullptr || remote_bytes == nullptr,
+                  PRISM_ERR_INVALID_ARG);
+  if (T > 0)
+    PRISM_RETURN_IF(topk_idx == nullptr || local_src == nullptr || remote_src == nullptr,
+                    PRISM_ERR_INVALID_ARG);
+  Workspace ws;
+  PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
+  return launch_dispatch(*desc, topk_idx, local_mask, T, local_src, local_offsets, remote_src,
+                         remote_offsets, n_local_remote, remote_bytes, nullptr, ws.block_hist,
+                         (hipStream_t)stream);
+}
+
+prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
+                              const prism_expert_weights* weights, const int32_t* local_src,
+                              const int32_t* local_offsets, int32_t T, void* y, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  PRISM_TRY(validate_desc(desc, T, true));
+  PRISM_TRY(check_weights(*desc, weights));
+  PRISM_RETURN_IF(local_offsets == nullptr, PRISM_ERR_INVALID_ARG);
+  if (T > 0) PRISM_RETURN_IF(x == nullptr || local_src == nullptr || y == nullptr, PRISM_ERR_INVALID_ARG);
+  Workspace ws;
+  PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
+  return launch_expert_ffn(*desc, x, *weights, local_src, local_offsets, T, y, ws.h, ws.tiles,
+                           (hipStream_t)stream);
+}
+
+prism_status prism_combine(const prism_layer_desc* desc, const void* y, const int32_t* local_src,
+                           const int32_t* local_offsets, const float* topk_gate, int32_t T,
+                           void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  PRISM_TRY(validate_desc(desc, T, true));
+  PRISM_RETURN_IF(local_offsets == nullptr, PRISM_ERR_INVALID_ARG);
+  if (T > 0)
+    PRISM_RETURN_IF(y == nullptr || local_src == nullptr || topk_gate == nullptr || out == nullptr,
+                    PRISM_ERR_INVALID_ARG);
+  Workspace ws;
+  PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
+  const hipStream_t st = (hipStream_t)stream;
+  PRISM_TRY(launch_build_inverse(*desc, local_src, local_offsets, T, ws.inv, st));
+  return launch_combine(*desc, y, ws.inv, topk_gate, T, out, st);
+}
+
+prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const void* w_router,
+                             const float* router_bias, const prism_expert_weights* weights,
+                             const uint8_t* local_mask, int32_t T, void* out, int32_t* topk_idx,
+                             float* topk_gate, int32_t* counts, int64_t* counts_accum,
+                             int32_t* remote_src, int32_t* remote_offsets,
+                             int32_t* n_local_remote, int64_t* remote_bytes, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  PRISM_TRY(validate_desc(desc, T, true));
+  PRISM_TRY(check_weights(*desc, weights));
+  PRISM_RETURN_IF(local_mask == nullptr || counts == nullptr || remote_offsets == nullptr ||
+                      n_local_remote == nullptr || remote_bytes == nullptr,
+                  PRISM_ERR_INVALID_ARG);
+  if (T > 0)
+    PRISM_RETURN_IF(x == nullptr || w_router == nullptr || out == nullptr || topk_idx == nullptr ||
+                        topk_gate == nullptr || remote_src == nullptr,
+                    PRISM_ERR_INVALID_ARG);
+  Workspace ws;
+  PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
+  const hipStream_t st = (hipStream_t)stream;
+  PRISM_TRY(launch_route(*desc, x, w_router, router_bias, T, nullptr, topk_idx, topk_gate, counts,
+                         counts_accum, st));
+  PRISM_TRY(launch_dispatch(*desc, topk_idx, local_mask, T, ws.local_src, ws.local_offsets,
+                            remote_src, remote_offsets, n_local_remote, remote_bytes, ws.inv,
+                            ws.block_hist, st));
+  PRISM_TRY(launch_expert_ffn(*desc, x, *weights, ws.local_src, ws.local_offsets, T, ws.y, ws.h,
+                              ws.tiles, st));
+  return launch_combine(*desc, ws.y, ws.inv, topk_gate, T, out, st);
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,111 @@
+// Gate-weighted aggregation of the local expert outputs (paper Sec. III-A: the
+// results of the experts are aggregated before the next block).  Remote slots
+// contribute nothing here; their rows arrive later in the real system.
+//
+//   out[t] = sum_{j local, ascending} gate[t,j] * y[inv[t*k+j]] + sum_s y[A + s*T + t]
+//
+// fp32 accumulation, one rounding to the layer dtype.  HBM-bound: every thread
+// moves 16 bytes per y row it touches.
+#include "prism_internal.h"
+
+namespace prism {
+namespace {
+
+__global__ void scatter_inverse_kernel(const int32_t* __restrict__ local_src,
+                                       const int32_t* __restrict__ local_offsets, int E, int A,
+                                       int32_t* __restrict__ inv) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r < A && r < local_offsets[E]) inv[local_src[r]] = r;
+}
+
+template <typename T> struct Vec;
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  __device__ static void load(const float* p, float (&v)[N]) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(p);
+    v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3];
+  }
+  __device__ static void store(float* p, const float (&v)[N]) {
+    *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
+  }
+};
+template <> struct Vec<uint16_t> {
+  static constexpr int N = 8;
+  __device__ static void load(const uint16_t* p, float (&v)[N]) {
+    const uint4 a = *reinterpret_cast<const uint4*>(p);
+    v[0] = bf16_lo(a.x); v[1] = bf16_hi(a.x); v[2] = bf16_lo(a.y); v[3] = bf16_hi(a.y);
+    v[4] = bf16_lo(a.z); v[5] = bf16_hi(a.z); v[6] = bf16_lo(a.w); v[7] = bf16_hi(a.w);
+  }
+  __device__ static void store(uint16_t* p, const float (&v)[N]) {
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < N; ++i) o[i] = (bf16_t)v[i];
+    *reinterpret_cast<bf16x8*>(p) = o;
+  }
+};
+
+template <typename TIO>
+__global__ __launch_bounds__(256) void combine_kernel(const TIO* __restrict__ y,
+                                                      const int32_t* __restrict__ inv,
+                                                      const float* __restrict__ gate, int T, int H,
+                                                      int k, int S, TIO* __restrict__ out) {
+  constexpr int N = Vec<TIO>::N;
+  const int vec_per_row = H / N;
+  const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long long)T * vec_per_row) return;
+  const int t = (int)(gid / vec_per_row);
+  const int col = (int)(gid - (long long)t * vec_per_row) * N;
+  float acc[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) acc[i] = 0.f;
+  for (int j = 0; j < k; ++j) {
+    const int row = inv[t * k + j];
+    if (row >= 0) {
+      const float gt = gate[t * k + j];
+      float v[N];
+      Vec<TIO>::load(y + (size_t)row * H + col, v);
+#pragma unroll
+      for (int i = 0; i < N; ++i) acc[i] = fmaf(gt, v[i], acc[i]);
+    }
+  }
+  const size_t A = (size_t)T * k;
+  for (int s = 0; s < S; ++s) {
+    float v[N];
+    Vec<TIO>::load(y + (A + (size_t)s * T + t) * H + col, v);
+#pragma unroll
+    for (int i = 0; i < N; ++i) acc[i] += v[i];
+  }
+  Vec<TIO>::store(out + (size_t)t * H + col, acc);
+}
+
+}  // namespace
+
+prism_status launch_build_inverse(const prism_layer_desc& d, const int32_t* local_src,
+                                  const int32_t* local_offsets, int T, int32_t* inv,
+                                  hipStream_t st) {
+  const int A = T * d.top_k;
+  if (A == 0) return PRISM_OK;
+  PRISM_TRY(launch_fill_i32(inv, A, -1, st));
+  hipLaunchKernelGGL(scatter_inverse_kernel, dim3(ceil_div(A, 256)), dim3(256), 0, st, local_src,
+                     local_offsets, d.n_experts, A, inv);
+  PRISM_CHECK_LAUNCH();
+  return PRISM_OK;
+}
+
+prism_status launch_combine(const prism_layer_desc& d, const void* y, const int32_t* inv,
+                            const float* topk_gate, int T, void* out, hipStream_t st) {
+  if (T == 0) return PRISM_OK;
+  const int n = d.dtype == PRISM_F32 ? 4 : 8;
+  const long long threads = (long long)T * (d.hidden / n);
+  const unsigned blocks = (unsigned)((threads + 255) / 256);
+  if (d.dtype == PRISM_F32)
+    hipLaunchKernelGGL(combine_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)y, inv,
+                       topk_gate, T, d.hidden, d.top_k, d.n_shared, (float*)out);
+  else
+    hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)y,
+                       inv, topk_gate, T, d.hidden, d.top_k, d.n_shared, (uint16_t*)out);
+  PRISM_CHECK_LAUNCH();
+  return PRISM_OK;
+}
+
+}  // namespace prism

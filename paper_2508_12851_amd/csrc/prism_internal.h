@@ -1,0 +1,126 @@
+// Internal declarations shared by the HIP translation units of libprism.
+#ifndef PRISM_INTERNAL_H_
+#define PRISM_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "prism.h"
+
+namespace prism {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ---------------------------------------------------------------------------
+// Workspace layout.  One layout serves every entry point, so a buffer sized by
+// prism_workspace_bytes() fits all of them.
+// ---------------------------------------------------------------------------
+constexpr int kDispatchChunk = 2048;   // assignments per dispatch block
+constexpr int kMaxTileM = 256;         // largest row tile of the grouped GEMM
+constexpr int kMinTileM = 16;          // smallest row tile (bounds the tile-table size)
+
+struct Workspace {
+  int32_t* local_src;      // [A]
+  int32_t* local_offsets;  // [E+1]
+  int32_t* inv;            // [A]  row of assignment a in y, or -1 when remote
+  int32_t* block_hist;     // [n_chunks * E]
+  int32_t* tiles;          // 2 x [tile_table_ints]: tile tables of the two grouped GEMMs
+  void* h;                 // [(A + S*T) * F] layer dtype: silu(gate)*up
+  void* y;                 // [(A + S*T) * H] layer dtype: expert outputs
+  size_t total;
+};
+
+static inline int elem_size(int dtype) { return dtype == PRISM_F32 ? 4 : 2; }
+
+static inline int max_tiles(const prism_layer_desc& d, int T) {
+  long long A = (long long)T * d.top_k;
+  return (int)(A / kMinTileM + d.n_experts + (long long)d.n_shared * ceil_div(T > 0 ? T : 1, kMinTileM) + 1);
+}
+
+// ints in one tile table: [0] = number of tiles, then 4 ints per tile
+static inline size_t tile_table_ints(const prism_layer_desc& d, int T) {
+  return align_up(4 + 4 * (size_t)max_tiles(d, T), 64);
+}
+
+static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
+  Workspace w;
+  const size_t A = (size_t)T * d.top_k;
+  const size_t rows = A + (size_t)d.n_shared * T;
+  const size_t es = elem_size(d.dtype);
+  const int n_chunks = ceil_div((int)(A > 0 ? A : 1), kDispatchChunk);
+  char* p = (char*)base;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* q = p ? p + off : nullptr; off += align_up(bytes ? bytes : 1, 256); return (void*)q; };
+  w.local_src = (int32_t*)take(A * 4);
+  w.local_offsets = (int32_t*)take((size_t)(d.n_experts + 1) * 4);
+  w.inv = (int32_t*)take(A * 4);
+  w.block_hist = (int32_t*)take((size_t)n_chunks * d.n_experts * 4);
+  w.tiles = (int32_t*)take(2 * tile_table_ints(d, T) * 4);
+  w.h = take(rows * d.ffn * es);
+  w.y = take(rows * d.hidden * es);
+  w.total = off;
+  return w;
+}
+
+// ---------------------------------------------------------------------------
+// Validation and launch helpers.
+// ---------------------------------------------------------------------------
+prism_status validate_desc(const prism_layer_desc* d, int32_t T, bool need_ffn_shapes);
+
+#define PRISM_RETURN_IF(cond, code) do { if (cond) return (code); } while (0)
+#define PRISM_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return PRISM_ERR_LAUNCH; } while (0)
+#define PRISM_TRY(expr) do { prism_status s__ = (expr); if (s__ != PRISM_OK) return s__; } while (0)
+
+// ---------------------------------------------------------------------------
+// Stage entry points used by the public API (all enqueue only).
+// ---------------------------------------------------------------------------
+prism_status launch_route(const prism_layer_desc& d, const void* x, const void* w_router,
+                          const float* bias, int T, float* logits, int32_t* topk_idx,
+                          float* topk_gate, int32_t* counts, int64_t* counts_accum,
+                          hipStream_t st);
+
+// inv may be NULL.
+prism_status launch_dispatch(const prism_layer_desc& d, const int32_t* topk_idx,
+                             const uint8_t* mask, int T, int32_t* local_src,
+                             int32_t* local_offsets, int32_t* remote_src, int32_t* remote_offsets,
+                             int32_t* n_local_remote, int64_t* remote_bytes, int32_t* inv,
+                             int32_t* block_hist, hipStream_t st);
+
+prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
+                               const prism_expert_weights& w, const int32_t* local_src,
+                               const int32_t* local_offsets, int T, void* y, void* h,
+                               int32_t* tiles, hipStream_t st);
+
+prism_status launch_fill_i32(int32_t* p, int n, int32_t v, hipStream_t st);
+
+// Builds inv from local_src/local_offsets (fill -1, then scatter).
+prism_status launch_build_inverse(const prism_layer_desc& d, const int32_t* local_src,
+                                  const int32_t* local_offsets, int T, int32_t* inv,
+                                  hipStream_t st);
+
+prism_status launch_combine(const prism_layer_desc& d, const void* y, const int32_t* inv,
+                            const float* topk_gate, int T, void* out, hipStream_t st);
+
+// ---------------------------------------------------------------------------
+// Device helpers.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __uint_as_float((uint32_t)b << 16);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+}  // namespace prism
+#endif  // PRISM_INTERNAL_H_

@@ -1,0 +1,58 @@
+"""Helpers shared by the GPU parity tests: upload seeded inputs, run the oracle."""
+import numpy as np
+import torch
+
+import paper_2508_12851_amd as P
+from oracle import prism_oracle as O
+
+
+def to_dev(a: np.ndarray) -> torch.Tensor:
+    """numpy -> device tensor; uint16 arrays are bf16 bit patterns."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def to_f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def desc_of(cfg):
+    return P.make_desc(cfg.H, cfg.F, cfg.E, cfg.k, cfg.S, cfg.dtype, cfg.bias_group_tokens)
+
+
+def weight_table(inp, mask=None, all_experts=False):
+    """Upload hosted experts (None for the others) and the shared experts."""
+    c = inp.cfg
+    mask = inp.mask if mask is None else mask
+    experts = []
+    for e in range(c.E):
+        if all_experts or mask[e]:
+            experts.append(tuple(to_dev(w) for w in inp.expert(e)))
+        else:
+            experts.append(None)
+    shared = [tuple(to_dev(w) for w in inp.shared(s)) for s in range(c.S)]
+    return P.WeightTable(experts, shared)
+
+
+def oracle_layer(inp, mask=None, x=None, token_pos=None):
+    c = inp.cfg
+    f = inp.f32
+    return O.moe_layer(f(inp.x) if x is None else x, f(inp.w_router), inp.bias,
+                       lambda e: tuple(f(w) for w in inp.expert(e)),
+                       [tuple(f(w) for w in inp.shared(s)) for s in range(c.S)],
+                       inp.mask if mask is None else mask, c.k, c.dtype, c.bias_group_tokens,
+                       token_pos)
+
+
+def rel_err(a, ref):
+    """max |a - ref| / (|ref| + rms(ref)): the layer-output error measure."""
+    a = np.asarray(a, np.float64)
+    ref = np.asarray(ref, np.float64)
+    rms = np.sqrt(np.mean(ref ** 2)) if ref.size else 0.0
+    if ref.size == 0:
+        return 0.0
+    return float(np.max(np.abs(a - ref) / (np.abs(ref) + rms + 1e-300)))
+
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}

@@ -1,0 +1,76 @@
+"""The C-ABI library builds, loads and exports every symbol include/prism.h declares;
+host-side validation returns error codes (no kernel is launched in these tests)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2508_12851_amd as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "prism.h")).read()
+    return sorted(set(re.findall(r"\b(prism_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = P.load_library()
+    declared = _declared_symbols()
+    assert sorted(P.SYMBOLS) == declared
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings():
+    lib = P.load_library()
+    assert lib.prism_status_string(0) == b"ok"
+    texts = {lib.prism_status_string(i) for i in range(5)}
+    assert len(texts) == 5 and all(texts)
+
+
+def test_workspace_bytes_grows_with_tokens_and_is_aligned():
+    d = P.make_desc(4096, 14336, 8, 2, 0, "bf16")
+    small, big = P.workspace_bytes(d, 32), P.workspace_bytes(d, 4096)
+    assert 0 < small < big and small % 256 == 0 and big % 256 == 0
+    # h and y for T*k rows dominate: (8192*14336 + 8192*4096) * 2 bytes
+    assert big >= (8192 * 14336 + 8192 * 4096) * 2
+    assert P.workspace_bytes(d, 0) > 0
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(top_k=0), 1), (dict(top_k=9, n_experts=8), 1), (dict(n_experts=257), 2),
+    (dict(top_k=9, n_experts=16), 2), (dict(hidden=100), 2), (dict(ffn=100), 2),
+    (dict(n_shared=17), 2), (dict(dtype_code=7), 1),
+])
+def test_validation_error_codes(kw, status):
+    base = dict(hidden=128, ffn=128, n_experts=8, top_k=2, n_shared=0, dtype_code=1)
+    base.update(kw)
+    d = P.LayerDesc(base["hidden"], base["ffn"], base["n_experts"], base["top_k"],
+                    base["n_shared"], base["dtype_code"], 0)
+    n = ctypes.c_size_t(0)
+    assert P.load_library().prism_workspace_bytes(ctypes.byref(d), 16, ctypes.byref(n)) == status
+
+
+def test_null_pointers_and_negative_tokens_are_rejected_before_any_launch():
+    lib = P.load_library()
+    d = P.make_desc(128, 128, 8, 2, 0, "bf16")
+    n = ctypes.c_size_t(0)
+    assert lib.prism_workspace_bytes(ctypes.byref(d), -1, ctypes.byref(n)) == 1
+    assert lib.prism_workspace_bytes(ctypes.byref(d), 16, None) == 1
+    assert lib.prism_workspace_bytes(None, 16, ctypes.byref(n)) == 1
+    # counts == NULL
+    assert lib.prism_route(ctypes.byref(d), None, None, None, 4, None, None, None, None, None, None) == 1
+    # required outputs NULL
+    assert lib.prism_dispatch(ctypes.byref(d), None, None, 4, None, None, None, None, None, None,
+                              None, 0, None) == 1
+    w = P.ExpertWeights()
+    assert lib.prism_expert_ffn(ctypes.byref(d), None, ctypes.byref(w), None, None, 4, None, None, 0,
+                                None) == 1
+    assert lib.prism_combine(ctypes.byref(d), None, None, None, None, 4, None, None, 0, None) == 1
+    assert lib.prism_moe_layer(ctypes.byref(d), None, None, None, None, None, 4, None, None, None,
+                               None, None, None, None, None, None, None, 0, None) == 1
+    with pytest.raises(P.PrismError):
+        P.workspace_bytes(P.make_desc(100, 128, 8, 2), 4)

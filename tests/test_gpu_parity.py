@@ -1,0 +1,278 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Bars: bit-exact routing indices, counts, permutation, offsets, remote list and
+byte counts; gates within 1e-6; outputs within max relative error 1e-4 (fp32)
+or 2e-2 (bf16), measured as max |a - ref| / (|ref| + rms(ref)).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2508_12851_amd as P
+from oracle import prism_oracle as O
+from prism_inputs import make_config, make_inputs
+
+from gpu_util import TOL, desc_of, oracle_layer, rel_err, to_dev, to_f32, weight_table
+
+pytestmark = pytest.mark.gpu
+
+
+# scaled-down versions of the five workloads: several tiles plus a ragged tail
+CASES = {
+    "tiny_f32": dict(name="cfg1_tiny_f32"),
+    "f32_ragged": dict(name="cfg1_tiny_f32", T=77, H=136, F=200, E=8, k=2),
+    "mixtral_small": dict(name="cfg2_mixtral_prefill", T=333, H=256, F=448),
+    "mixtral_decode_small": dict(name="cfg3_mixtral_decode", T=32, H=256, F=448),
+    "finegrained_small": dict(name="cfg4_finegrained", T=700, H=128, F=192, bias_group_tokens=128),
+    "dsv2_small": dict(name="cfg5_dsv2lite_migration", T=515, H=128, F=192),
+}
+
+
+def _inputs(case, phase=0):
+    kw = dict(CASES[case])
+    cfg = make_config(kw.pop("name"), **kw)
+    return cfg, make_inputs(cfg, phase=phase)
+
+
+def _select_from_logits(logits, k):
+    """Descending logit, ascending index on ties (stable sort on -logit)."""
+    order = np.argsort(-logits.astype(np.float64), axis=1, kind="stable")
+    return order[:, :k].astype(np.int32)
+
+
+# ---------------------------------------------------------------------------
+# route
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_route_parity(case):
+    cfg, inp = _inputs(case)
+    desc = desc_of(cfg)
+    ref = O.route(inp.f32(inp.x), inp.f32(inp.w_router), inp.bias, cfg.k, cfg.bias_group_tokens)
+    acc = torch.zeros(cfg.E, dtype=torch.int64, device="cuda")
+    for _ in range(2):
+        got = P.prism_route(desc, to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias),
+                            counts_accum=acc)
+    torch.cuda.synchronize()
+    logits = got.logits.cpu().numpy()
+    idx = got.topk_idx.cpu().numpy()
+    print(f"{case}: max |logit_gpu - logit_oracle| = {np.max(np.abs(logits - ref.logits)):.3g}")
+    assert np.array_equal(idx, ref.topk_idx)
+    assert np.array_equal(got.counts.cpu().numpy(), ref.counts)
+    assert np.array_equal(acc.cpu().numpy(), 2 * ref.counts.astype(np.int64))
+    # selection checked independently of accumulation: GPU logits -> plain selection
+    assert np.array_equal(idx, _select_from_logits(logits, cfg.k))
+    assert np.max(np.abs(logits - ref.logits)) <= 1e-6 * max(1.0, np.max(np.abs(ref.logits)))
+    gate = got.topk_gate.cpu().numpy()
+    assert np.max(np.abs(gate - ref.topk_gate)) <= 1e-6
+    assert np.max(np.abs(gate.astype(np.float64).sum(axis=1) - 1.0)) <= 1e-6
+
+
+@pytest.mark.parametrize("E,k,T", [(256, 8, 130), (129, 7, 64), (17, 1, 5), (3, 3, 1)])
+def test_route_wide_expert_counts_and_ties(E, k, T):
+    rng = np.random.default_rng(E * 1000 + k)
+    H = 64
+    x = rng.standard_normal((T, H)).astype(np.float32)
+    w = rng.standard_normal((E, H)).astype(np.float32) / 8
+    if E >= 8:
+        w[E - 2] = w[1]           # exact ties between experts 1 and E-2
+        w[5] = w[1]
+    bias = rng.standard_normal((1, E)).astype(np.float32)
+    bias[0, E - 2] = bias[0, 1]
+    if E >= 8:
+        bias[0, 5] = bias[0, 1]
+    desc = P.make_desc(H, 64, E, k, 0, "f32", 0)
+    ref = O.route(x, w, bias, k)
+    got = P.prism_route(desc, to_dev(x), to_dev(w), to_dev(bias))
+    assert np.array_equal(got.topk_idx.cpu().numpy(), ref.topk_idx)
+    assert np.array_equal(got.counts.cpu().numpy(), ref.counts)
+    assert np.max(np.abs(got.topk_gate.cpu().numpy() - ref.topk_gate)) <= 1e-6
+
+
+def test_route_zero_tokens_and_no_bias():
+    desc = P.make_desc(64, 64, 8, 2, 0, "f32", 0)
+    x = torch.empty((0, 64), device="cuda")
+    w = torch.randn((8, 64), device="cuda")
+    got = P.prism_route(desc, x, w, None)
+    assert got.counts.cpu().tolist() == [0] * 8
+    xs = np.random.default_rng(1).standard_normal((40, 64)).astype(np.float32)
+    ref = O.route(xs, to_f32(w), None, 2)
+    got = P.prism_route(desc, to_dev(xs), w, None)
+    assert np.array_equal(got.topk_idx.cpu().numpy(), ref.topk_idx)
+
+
+# ---------------------------------------------------------------------------
+# dispatch
+# ---------------------------------------------------------------------------
+
+def _check_dispatch(desc, idx, mask, H, es):
+    ref = O.dispatch(idx, mask, H, es)
+    ws = P.alloc_workspace(desc, idx.shape[0])
+    got = P.prism_dispatch(desc, to_dev(idx), to_dev(mask), ws)
+    got2 = P.prism_dispatch(desc, to_dev(idx), to_dev(mask), ws)
+    torch.cuda.synchronize()
+    nl, nr = got.n_local_remote.cpu().tolist()
+    assert (nl, nr) == (ref.n_local, ref.n_remote)
+    assert np.array_equal(got.local_offsets.cpu().numpy(), ref.local_offsets)
+    assert np.array_equal(got.remote_offsets.cpu().numpy(), ref.remote_offsets)
+    assert np.array_equal(got.local_src.cpu().numpy()[:nl], ref.local_src)
+    assert np.array_equal(got.remote_src.cpu().numpy()[:nr], ref.remote_src)
+    assert np.all(got.local_src.cpu().numpy()[nl:] == -1)          # entries past n_local untouched
+    assert np.array_equal(got.remote_bytes.cpu().numpy(), ref.remote_bytes)
+    assert torch.equal(got.local_src, got2.local_src) and torch.equal(got.remote_src, got2.remote_src)
+
+
+@pytest.mark.parametrize("T,E,k,p_local", [(64, 8, 2, 0.5), (4096, 8, 2, 0.6), (5000, 60, 4, 0.6),
+                                           (3001, 64, 6, 0.5), (1500, 256, 8, 0.3), (1, 4, 4, 0.5),
+                                           (700, 8, 2, 1.0), (700, 8, 2, 0.0)])
+def test_dispatch_parity(T, E, k, p_local):
+    rng = np.random.default_rng(T + E)
+    # skewed popularity so buckets have very different sizes
+    pop = 1.0 / np.arange(1, E + 1)
+    pop /= pop.sum()
+    idx = np.stack([rng.choice(E, size=k, replace=False, p=pop) for _ in range(T)]).astype(np.int32)
+    mask = (rng.random(E) < p_local).astype(np.uint8)
+    desc = P.make_desc(64, 64, E, k, 0, "bf16", 0)
+    _check_dispatch(desc, idx, mask, 64, 2)
+
+
+def test_dispatch_zero_tokens():
+    desc = P.make_desc(64, 64, 8, 2, 0, "bf16", 0)
+    ws = P.alloc_workspace(desc, 0)
+    got = P.prism_dispatch(desc, torch.empty((0, 2), dtype=torch.int32, device="cuda"),
+                           torch.ones(8, dtype=torch.uint8, device="cuda"), ws)
+    assert got.local_offsets.cpu().tolist() == [0] * 9
+    assert got.n_local_remote.cpu().tolist() == [0, 0]
+    assert got.remote_bytes.cpu().tolist() == [0, 0]
+
+
+# ---------------------------------------------------------------------------
+# expert FFN and combine, as separate calls
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_expert_ffn_and_combine_parity(case):
+    cfg, inp = _inputs(case)
+    desc = desc_of(cfg)
+    f = inp.f32
+    r = O.route(f(inp.x), f(inp.w_router), inp.bias, cfg.k, cfg.bias_group_tokens)
+    d = O.dispatch(r.topk_idx, inp.mask, cfg.H, cfg.es)
+    shared = [tuple(f(w) for w in inp.shared(s)) for s in range(cfg.S)]
+    y_ref = O.expert_ffn(f(inp.x), lambda e: tuple(f(w) for w in inp.expert(e)), shared,
+                         d.local_src, d.local_offsets, cfg.k)
+    out_ref = O.combine(y_ref, d.local_src, r.topk_gate, cfg.T, cfg.S, cfg.dtype)
+
+    ws = P.alloc_workspace(desc, cfg.T)
+    wt = weight_table(inp)
+    A = cfg.A
+    local_src = np.full(A, -1, np.int32)
+    local_src[:d.n_local] = d.local_src
+    y = P.prism_expert_ffn(desc, to_dev(inp.x), wt, to_dev(local_src), to_dev(d.local_offsets), ws)
+    torch.cuda.synchronize()
+    yg = to_f32(y)
+    y_got = np.concatenate([yg[:d.n_local], yg[A:]])            # shared rows start at T*k
+    assert rel_err(y_got, y_ref) <= TOL[cfg.dtype], rel_err(y_got, y_ref)
+    assert np.all(yg[d.n_local:A] == 0)                         # rows past n_local untouched
+
+    out = P.prism_combine(desc, y, to_dev(local_src), to_dev(d.local_offsets),
+                          to_dev(r.topk_gate), ws)
+    torch.cuda.synchronize()
+    err = rel_err(to_f32(out), out_ref)
+    print(f"{case}: y err {rel_err(y_got, y_ref):.3g}, out err {err:.3g}")
+    assert err <= TOL[cfg.dtype], err
+
+
+# ---------------------------------------------------------------------------
+# the whole layer
+# ---------------------------------------------------------------------------
+
+def _run_layer(cfg, inp, mask=None, wt=None):
+    desc = desc_of(cfg)
+    ws = P.alloc_workspace(desc, cfg.T)
+    mask = inp.mask if mask is None else mask
+    wt = weight_table(inp, mask) if wt is None else wt
+    o = P.prism_moe_layer(desc, to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias), wt,
+                          to_dev(mask), ws)
+    torch.cuda.synchronize()
+    return o
+
+
+def _check_layer(cfg, o, ref):
+    nl, nr = o.n_local_remote.cpu().tolist()
+    assert np.array_equal(o.topk_idx.cpu().numpy(), ref.route.topk_idx)
+    assert np.array_equal(o.counts.cpu().numpy(), ref.route.counts)
+    assert np.max(np.abs(o.topk_gate.cpu().numpy() - ref.route.topk_gate)) <= 1e-6
+    assert (nl, nr) == (ref.dispatch.n_local, ref.dispatch.n_remote)
+    assert np.array_equal(o.remote_src.cpu().numpy()[:nr], ref.dispatch.remote_src)
+    assert np.array_equal(o.remote_offsets.cpu().numpy(), ref.dispatch.remote_offsets)
+    assert np.array_equal(o.remote_bytes.cpu().numpy(), ref.dispatch.remote_bytes)
+    err = rel_err(to_f32(o.out), ref.out)
+    assert err <= TOL[cfg.dtype], err
+    return err
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_moe_layer_parity(case):
+    cfg, inp = _inputs(case)
+    o = _run_layer(cfg, inp)
+    err = _check_layer(cfg, o, oracle_layer(inp))
+    print(f"{case}: layer out err {err:.3g}")
+
+
+def test_moe_layer_second_phase_mask_change():
+    cfg, p0 = _inputs("dsv2_small", 0)
+    _, p1 = _inputs("dsv2_small", 1)
+    for inp in (p0, p1):
+        _check_layer(cfg, _run_layer(cfg, inp), oracle_layer(inp))
+    # phase-1 tokens under the stale phase-0 mask: same routing, different split
+    a = _run_layer(cfg, p1, mask=p0.mask)
+    b = _run_layer(cfg, p1)
+    assert torch.equal(a.topk_idx, b.topk_idx) and torch.equal(a.counts, b.counts)
+    assert a.n_local_remote.cpu().tolist() != b.n_local_remote.cpu().tolist()
+
+
+def test_moe_layer_mask_extremes_and_complement():
+    cfg, inp = _inputs("finegrained_small")
+    ones = np.ones(cfg.E, np.uint8)
+    zeros = np.zeros(cfg.E, np.uint8)
+    wt_all = weight_table(inp, all_experts=True)
+    full = _run_layer(cfg, inp, ones, wt_all)
+    _check_layer(cfg, full, oracle_layer(inp, ones))
+    assert full.n_local_remote.cpu().tolist() == [cfg.A, 0]
+    none = _run_layer(cfg, inp, zeros, wt_all)
+    _check_layer(cfg, none, oracle_layer(inp, zeros))
+    assert none.n_local_remote.cpu().tolist() == [0, cfg.A]
+    assert int(none.remote_bytes.sum()) == 2 * cfg.A * cfg.H * cfg.es
+    # local partial + remote partial - shared counted twice = full layer
+    a = to_f32(_run_layer(cfg, inp, inp.mask, wt_all).out).astype(np.float64)
+    b = to_f32(_run_layer(cfg, inp, 1 - inp.mask, wt_all).out).astype(np.float64)
+    assert rel_err(a + b - to_f32(none.out), to_f32(full.out)) <= 2 * TOL[cfg.dtype]
+
+
+def test_moe_layer_is_deterministic_and_reuses_workspace():
+    cfg, inp = _inputs("mixtral_small")
+    desc = desc_of(cfg)
+    ws = P.alloc_workspace(desc, cfg.T)
+    wt = weight_table(inp)
+    args = (desc, to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias), wt, to_dev(inp.mask), ws)
+    a = P.prism_moe_layer(*args)
+    ws.fill_(0xFF)                       # stale workspace contents must not matter
+    b = P.prism_moe_layer(*args)
+    torch.cuda.synchronize()
+    for name in ("topk_idx", "counts", "remote_offsets", "n_local_remote", "remote_bytes", "out"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    nr = int(a.n_local_remote[1])
+    assert torch.equal(a.remote_src[:nr], b.remote_src[:nr])
+
+
+def test_moe_layer_zero_tokens():
+    cfg, inp = _inputs("mixtral_small")
+    desc = desc_of(cfg)
+    ws = P.alloc_workspace(desc, 0)
+    o = P.prism_moe_layer(desc, torch.empty((0, cfg.H), dtype=torch.bfloat16, device="cuda"),
+                          to_dev(inp.w_router), to_dev(inp.bias), weight_table(inp),
+                          to_dev(inp.mask), ws)
+    torch.cuda.synchronize()
+    assert o.counts.cpu().tolist() == [0] * cfg.E
+    assert o.n_local_remote.cpu().tolist() == [0, 0]
+    assert o.remote_offsets.cpu().tolist() == [0] * (cfg.E + 1)
