@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the placement-aware MoE layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME]
+
+A step is one call of prism_moe_layer (route -> dispatch -> grouped SwiGLU FFN
+over the local experts -> combine) on one batch of seeded synthetic input that
+is already resident in HBM.  Prints ONE JSON line: whole-job tokens/s, the
+roofline fraction of the dominant kernel (timed with HIP events recorded by the
+library around that kernel on the launch stream) and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
+DEFAULT_CONFIG = "cfg2_mixtral_prefill"
+DECODE_WEIGHT_COPIES = 4           # rotate weight copies so the 256 MB last-level cache cannot help
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            return float(line.split("=")[1])
+    return None
+
+
+def cpu_baseline(inp, n_sample: int):
+    """Time the CPU oracle, as it stands, on the first n_sample tokens of the workload."""
+    from oracle import prism_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = len(os.sched_getaffinity(0))
+    c = inp.cfg
+    f = inp.f32
+    n = min(n_sample, c.T)
+    xs = f(inp.x)[:n]
+    t0 = time.perf_counter()
+    O.moe_layer(xs, f(inp.w_router), inp.bias, lambda e: tuple(f(w) for w in inp.expert(e)),
+                [tuple(f(w) for w in inp.shared(s)) for s in range(c.S)], inp.mask, c.k, c.dtype,
+                c.bias_group_tokens, np.arange(n))
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n} of {c.T} tokens of {c.name}, whole layer, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", default=DEFAULT_CONFIG)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--trace-all", action="store_true", help="also time every stage (stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    import paper_2508_12851_amd as P
+    from prism_inputs import CONFIGS, make_inputs
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    cfg = CONFIGS[args.config]
+    decode = cfg.T <= 64
+    steps = args.steps if args.steps is not None else (200 if decode else 30)
+    warmup = args.warmup if args.warmup is not None else (20 if decode else 5)
+
+    t0 = time.perf_counter()
+    inp = make_inputs(cfg, weights="local", threads=16)
+    log(f"[bench] generated {cfg.name} inputs in {time.perf_counter() - t0:.1f} s")
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(a).cuda()
+
+    desc = P.make_desc(cfg.H, cfg.F, cfg.E, cfg.k, cfg.S, cfg.dtype, cfg.bias_group_tokens)
+    experts = [tuple(dev(w) for w in inp.expert(e)) if inp.mask[e] else None for e in range(cfg.E)]
+    shared = [tuple(dev(w) for w in inp.shared(s)) for s in range(cfg.S)]
+    tables = [P.WeightTable(experts, shared)]
+    if decode:
+        for _ in range(DECODE_WEIGHT_COPIES - 1):
+            ex = [None if t is None else tuple(w.clone() for w in t) for t in experts]
+            sh = [tuple(w.clone() for w in t) for t in shared]
+            tables.append(P.WeightTable(ex, sh))
+    x, w_router, bias, mask = dev(inp.x), dev(inp.w_router), dev(inp.bias), dev(inp.mask)
+    ws = P.alloc_workspace(desc, cfg.T)
+    out = P.alloc_layer_out(desc, cfg.T)
+    torch.cuda.synchronize()
+
+    # one HIP event pair per timed step around the dominant kernel (gate/up grouped GEMM)
+    n_st = len(P.STAGES)
+    traced = range(n_st) if args.trace_all else (P.STAGES.index("ffn_up"),)
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(n_st)] for _ in range(steps)]
+    handle_arrays = []
+    for step_ev in events:
+        arr = (ctypes.c_void_p * (2 * n_st))()
+        for s in traced:
+            for j in (0, 1):
+                step_ev[s][j].record()               # materialise the hipEvent_t
+                arr[2 * s + j] = step_ev[s][j].cuda_event
+        handle_arrays.append(arr)
+    torch.cuda.synchronize()
+
+    def step(i, ev=None):
+        P.prism_moe_layer(desc, x, w_router, bias, tables[i % len(tables)], mask, ws, out,
+                          stage_events=ev)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i, handle_arrays[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / steps
+    tokens_per_s = cfg.T * steps / elapsed
+
+    stage_ms = {}
+    for s in traced:
+        stage_ms[P.STAGES[s]] = float(np.mean([events[i][s][0].elapsed_time(events[i][s][1])
+                                               for i in range(steps)]))
+    n_local, n_remote = out.n_local_remote.cpu().tolist()
+    counts = out.counts.cpu().numpy()
+    rows = n_local + cfg.S * cfg.T
+    es = cfg.es
+    dom_ms = stage_ms["ffn_up"]
+    if decode:
+        touched = int(np.sum((inp.mask == 1) & (counts > 0))) + cfg.S
+        alg_bytes = touched * 2 * cfg.H * cfg.F * es + cfg.T * cfg.H * es + rows * cfg.F * es
+        achieved = alg_bytes / (dom_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": read_traffic(cfg.name),
+                    "kernel": "grouped_gemm_kernel<gated> (gate/up projection + silu*up)",
+                    "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": dom_ms}
+    else:
+        alg_flop = 4.0 * cfg.H * cfg.F * rows
+        achieved = alg_flop / (dom_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_BF16_TFLOPS,
+                    "traffic": read_traffic(cfg.name),
+                    "kernel": "grouped_gemm_kernel<gated> (gate/up projection + silu*up)",
+                    "algorithmic_flop_per_launch": alg_flop, "kernel_ms": dom_ms}
+    layer_flop = 2.0 * cfg.T * cfg.H * cfg.E + 6.0 * cfg.H * cfg.F * rows
+    log(f"[bench] {cfg.name}: {ms_per_step:.3f} ms/step, {tokens_per_s:.4g} tokens/s, "
+        f"n_local={n_local} n_remote={n_remote} local ratio={n_local / max(1, cfg.A):.3f}, "
+        f"layer {layer_flop / (ms_per_step * 1e-3) / 1e12:.1f} TFLOP/s; stage ms: "
+        + ", ".join(f"{k}={v:.4f}" for k, v in stage_ms.items()))
+
+    result = {
+        "metric": "moe_layer_tokens_per_sec", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "tokens": cfg.T, "hidden": cfg.H, "ffn": cfg.F,
+                   "experts": cfg.E, "top_k": cfg.k, "shared_experts": cfg.S,
+                   "local_experts": int(inp.mask.sum()), "n_local": n_local, "n_remote": n_remote,
+                   "remote_bytes_each_way": int(out.remote_bytes[0]),
+                   "weight_copies_rotated": len(tables)},
+        "roofline": roofline,
+        "layer_tflops": layer_flop / (ms_per_step * 1e-3) / 1e12,
+    }
+    if not args.no_cpu_baseline:
+        n_sample = args.cpu_sample_tokens or (cfg.T if decode else 256)
+        result["cpu_baseline"] = cpu_baseline(inp, n_sample)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

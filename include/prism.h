@@ -189,6 +189,32 @@ prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const 
                              int32_t* n_local_remote, int64_t* remote_bytes, void* workspace,
                              size_t workspace_bytes, void* stream);
 
+/*
+ * prism_moe_layer with stage timing for measurement harnesses.  stage_events
+ * is a HOST array of 2 * PRISM_N_STAGES hipEvent_t handles (as void*), or
+ * NULL.  For stage s, if stage_events[2s] and stage_events[2s+1] are both
+ * non-NULL, the first is recorded on `stream` right before and the second
+ * right after that stage's kernels: the router kernel, the three dispatch
+ * kernels, the gate/up grouped GEMM alone, the down grouped GEMM alone, the
+ * combine kernel.  Nothing else differs from prism_moe_layer, which is this
+ * call with stage_events == NULL.
+ */
+#define PRISM_STAGE_ROUTE 0
+#define PRISM_STAGE_DISPATCH 1
+#define PRISM_STAGE_FFN_UP 2
+#define PRISM_STAGE_FFN_DOWN 3
+#define PRISM_STAGE_COMBINE 4
+#define PRISM_N_STAGES 5
+prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
+                                    const void* w_router, const float* router_bias,
+                                    const prism_expert_weights* weights,
+                                    const uint8_t* local_mask, int32_t T, void* out,
+                                    int32_t* topk_idx, float* topk_gate, int32_t* counts,
+                                    int64_t* counts_accum, int32_t* remote_src,
+                                    int32_t* remote_offsets, int32_t* n_local_remote,
+                                    int64_t* remote_bytes, void* workspace, size_t workspace_bytes,
+                                    void* stream, void* const* stage_events);
+
 #ifdef __cplusplus
 }
 #endif

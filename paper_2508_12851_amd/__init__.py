@@ -5,5 +5,5 @@ load the library; the first call (or load_library()) does."""
 from .binding import (  # noqa: F401
     ExpertWeights, LayerDesc, LayerOut, PrismError, WeightTable, alloc_layer_out, alloc_workspace,
     load_library, make_desc, prism_combine, prism_dispatch, prism_expert_ffn, prism_moe_layer,
-    prism_route, torch_dtype, workspace_bytes, LIB_PATH, SYMBOLS,
+    prism_route, torch_dtype, workspace_bytes, LIB_PATH, SYMBOLS, STAGES,
 )

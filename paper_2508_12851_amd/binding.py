@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_PKG, "libprism.so")
 
 PRISM_F32, PRISM_BF16 = 0, 1
 SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism_dispatch",
-           "prism_expert_ffn", "prism_combine", "prism_moe_layer")
+           "prism_expert_ffn", "prism_combine", "prism_moe_layer", "prism_moe_layer_traced")
+STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
 
 
 class PrismError(RuntimeError):
@@ -63,6 +64,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.prism_combine.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.prism_moe_layer.argtypes = [dp, vp, vp, vp, wp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                     vp, sz, vp]
+    lib.prism_moe_layer_traced.argtypes = lib.prism_moe_layer.argtypes + [vp]
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -227,9 +229,22 @@ def alloc_layer_out(desc: LayerDesc, T: int, device="cuda") -> LayerOut:
 
 def prism_moe_layer(desc: LayerDesc, x, w_router, router_bias, weights: WeightTable, local_mask,
                     workspace, outputs: Optional[LayerOut] = None, counts_accum=None,
-                    stream=None) -> LayerOut:
+                    stream=None, stage_events=None) -> LayerOut:
+    """stage_events: optional ctypes array of 2*len(STAGES) hipEvent_t handles (see prism.h)."""
     T = x.shape[0]
     o = alloc_layer_out(desc, T, x.device) if outputs is None else outputs
+    lib = load_library()
+    if stage_events is not None:
+        _check(lib.prism_moe_layer_traced(ctypes.byref(desc), _ptr(x), _ptr(w_router),
+                                          _ptr(router_bias), ctypes.byref(weights.struct),
+                                          _ptr(local_mask), T, _ptr(o.out), _ptr(o.topk_idx),
+                                          _ptr(o.topk_gate), _ptr(o.counts), _ptr(counts_accum),
+                                          _ptr(o.remote_src), _ptr(o.remote_offsets),
+                                          _ptr(o.n_local_remote), _ptr(o.remote_bytes),
+                                          _ptr(workspace), workspace.numel(), _stream(stream),
+                                          ctypes.cast(stage_events, ctypes.c_void_p)),
+               "prism_moe_layer_traced")
+        return o
     _check(load_library().prism_moe_layer(ctypes.byref(desc), _ptr(x), _ptr(w_router),
                                           _ptr(router_bias), ctypes.byref(weights.struct),
                                           _ptr(local_mask), T, _ptr(o.out), _ptr(o.topk_idx),

@@ -112,7 +112,7 @@ prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
   Workspace ws;
   PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
   return launch_expert_ffn(*desc, x, *weights, local_src, local_offsets, T, y, ws.h, ws.tiles,
-                           (hipStream_t)stream);
+                           (hipStream_t)stream, nullptr);
 }
 
 prism_status prism_combine(const prism_layer_desc* desc, const void* y, const int32_t* local_src,
@@ -130,13 +130,15 @@ prism_status prism_combine(const prism_layer_desc* desc, const void* y, const in
   return launch_combine(*desc, y, ws.inv, topk_gate, T, out, st);
 }
 
-prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const void* w_router,
-                             const float* router_bias, const prism_expert_weights* weights,
-                             const uint8_t* local_mask, int32_t T, void* out, int32_t* topk_idx,
-                             float* topk_gate, int32_t* counts, int64_t* counts_accum,
-                             int32_t* remote_src, int32_t* remote_offsets,
-                             int32_t* n_local_remote, int64_t* remote_bytes, void* workspace,
-                             size_t workspace_bytes, void* stream) {
+prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
+                                    const void* w_router, const float* router_bias,
+                                    const prism_expert_weights* weights,
+                                    const uint8_t* local_mask, int32_t T, void* out,
+                                    int32_t* topk_idx, float* topk_gate, int32_t* counts,
+                                    int64_t* counts_accum, int32_t* remote_src,
+                                    int32_t* remote_offsets, int32_t* n_local_remote,
+                                    int64_t* remote_bytes, void* workspace, size_t workspace_bytes,
+                                    void* stream, void* const* stage_events) {
   PRISM_TRY(validate_desc(desc, T, true));
   PRISM_TRY(check_weights(*desc, weights));
   PRISM_RETURN_IF(local_mask == nullptr || counts == nullptr || remote_offsets == nullptr ||
@@ -149,14 +151,35 @@ prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const 
   Workspace ws;
   PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
   const hipStream_t st = (hipStream_t)stream;
+  void* const* ev = stage_events;
+  trace(ev, PRISM_STAGE_ROUTE, 0, st);
   PRISM_TRY(launch_route(*desc, x, w_router, router_bias, T, nullptr, topk_idx, topk_gate, counts,
                          counts_accum, st));
+  trace(ev, PRISM_STAGE_ROUTE, 1, st);
+  trace(ev, PRISM_STAGE_DISPATCH, 0, st);
   PRISM_TRY(launch_dispatch(*desc, topk_idx, local_mask, T, ws.local_src, ws.local_offsets,
                             remote_src, remote_offsets, n_local_remote, remote_bytes, ws.inv,
                             ws.block_hist, st));
+  trace(ev, PRISM_STAGE_DISPATCH, 1, st);
   PRISM_TRY(launch_expert_ffn(*desc, x, *weights, ws.local_src, ws.local_offsets, T, ws.y, ws.h,
-                              ws.tiles, st));
-  return launch_combine(*desc, ws.y, ws.inv, topk_gate, T, out, st);
+                              ws.tiles, st, ev));
+  trace(ev, PRISM_STAGE_COMBINE, 0, st);
+  PRISM_TRY(launch_combine(*desc, ws.y, ws.inv, topk_gate, T, out, st));
+  trace(ev, PRISM_STAGE_COMBINE, 1, st);
+  return PRISM_OK;
+}
+
+prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const void* w_router,
+                             const float* router_bias, const prism_expert_weights* weights,
+                             const uint8_t* local_mask, int32_t T, void* out, int32_t* topk_idx,
+                             float* topk_gate, int32_t* counts, int64_t* counts_accum,
+                             int32_t* remote_src, int32_t* remote_offsets,
+                             int32_t* n_local_remote, int64_t* remote_bytes, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  return prism_moe_layer_traced(desc, x, w_router, router_bias, weights, local_mask, T, out,
+                                topk_idx, topk_gate, counts, counts_accum, remote_src,
+                                remote_offsets, n_local_remote, remote_bytes, workspace,
+                                workspace_bytes, stream, nullptr);
 }
 
 #pragma GCC visibility pop

@@ -367,7 +367,7 @@ __global__ __launch_bounds__(256) void ffn2_f32_kernel(const F32Args p) {
 prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
-                               int32_t* tiles, hipStream_t st) {
+                               int32_t* tiles, hipStream_t st, void* const* stage_events) {
   if (T == 0) return PRISM_OK;
   const int A = T * d.top_k;
   const int rows = A + d.n_shared * T;
@@ -376,12 +376,16 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
               w.shared_w_down, local_src, local_offsets, (float*)h, (float*)y,
               T, d.hidden, d.ffn, d.n_experts, d.n_shared, d.top_k};
     if ((size_t)d.hidden * 4 > 64 * 1024 || (size_t)d.ffn * 4 > 64 * 1024) return PRISM_ERR_UNSUPPORTED;
+    trace(stage_events, PRISM_STAGE_FFN_UP, 0, st);
     hipLaunchKernelGGL(ffn1_f32_kernel, dim3(rows, ceil_div(d.ffn, kF32ColsPerBlock)), dim3(256),
                        (size_t)d.hidden * 4, st, a);
     PRISM_CHECK_LAUNCH();
+    trace(stage_events, PRISM_STAGE_FFN_UP, 1, st);
+    trace(stage_events, PRISM_STAGE_FFN_DOWN, 0, st);
     hipLaunchKernelGGL(ffn2_f32_kernel, dim3(rows, ceil_div(d.hidden, kF32ColsPerBlock)), dim3(256),
                        (size_t)d.ffn * 4, st, a);
     PRISM_CHECK_LAUNCH();
+    trace(stage_events, PRISM_STAGE_FFN_DOWN, 1, st);
     return PRISM_OK;
   }
 
@@ -402,7 +406,9 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
   g1.tiles = tiles1; g1.local_src = local_src;
   g1.K = d.hidden; g1.N = d.ffn; g1.top_k = d.top_k; g1.E = d.n_experts;
   g1.n_ntiles = ceil_div(d.ffn, 64);
+  trace(stage_events, PRISM_STAGE_FFN_UP, 0, st);
   PRISM_TRY((launch_gemm<BM, 128, 2, 2, true>(g1, max_mtiles, st)));
+  trace(stage_events, PRISM_STAGE_FFN_UP, 1, st);
 
   GemmArgs g2{};
   g2.A = (const uint16_t*)h;
@@ -411,7 +417,9 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
   g2.tiles = tiles1; g2.local_src = local_src;
   g2.K = d.ffn; g2.N = d.hidden; g2.top_k = d.top_k; g2.E = d.n_experts;
   g2.n_ntiles = ceil_div(d.hidden, 128);
+  trace(stage_events, PRISM_STAGE_FFN_DOWN, 0, st);
   PRISM_TRY((launch_gemm<BM, 128, 2, 2, false>(g2, max_mtiles, st)));
+  trace(stage_events, PRISM_STAGE_FFN_DOWN, 1, st);
   return PRISM_OK;
 }
 

@@ -101,7 +101,13 @@ prism_status launch_dispatch(const prism_layer_desc& d, const int32_t* topk_idx,
 prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
-                               int32_t* tiles, hipStream_t st);
+                               int32_t* tiles, hipStream_t st, void* const* stage_events);
+
+// Records stage_events[2 * stage + end] on st when tracing is on and the pair is set.
+static inline void trace(void* const* ev, int stage, int end, hipStream_t st) {
+  if (ev != nullptr && ev[2 * stage] != nullptr && ev[2 * stage + 1] != nullptr)
+    (void)hipEventRecord((hipEvent_t)ev[2 * stage + end], st);
+}
 
 prism_status launch_fill_i32(int32_t* p, int n, int32_t v, hipStream_t st);
 
