@@ -28,15 +28,14 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // prism_workspace_bytes() fits all of them.
 // ---------------------------------------------------------------------------
 constexpr int kDispatchChunk = 2048;   // assignments per dispatch block
-constexpr int kMaxTileM = 256;         // largest row tile of the grouped GEMM
-constexpr int kMinTileM = 16;          // smallest row tile (bounds the tile-table size)
+constexpr int kMinTileM = 64;           // smallest row tile of the grouped GEMM (bounds table sizes)
 
 struct Workspace {
   int32_t* local_src;      // [A]
   int32_t* local_offsets;  // [E+1]
   int32_t* inv;            // [A]  row of assignment a in y, or -1 when remote
   int32_t* block_hist;     // [n_chunks * E]
-  int32_t* tiles;          // 2 x [tile_table_ints]: tile tables of the two grouped GEMMs
+  int32_t* tiles;          // 2 x [tile_table_ints]: schedules of the two grouped GEMMs
   void* h;                 // [(A + S*T) * F] layer dtype: silu(gate)*up
   void* y;                 // [(A + S*T) * H] layer dtype: expert outputs
   size_t total;
@@ -44,14 +43,13 @@ struct Workspace {
 
 static inline int elem_size(int dtype) { return dtype == PRISM_F32 ? 4 : 2; }
 
-static inline int max_tiles(const prism_layer_desc& d, int T) {
-  long long A = (long long)T * d.top_k;
-  return (int)(A / kMinTileM + d.n_experts + (long long)d.n_shared * ceil_div(T > 0 ? T : 1, kMinTileM) + 1);
-}
-
-// ints in one tile table: [0] = number of tiles, then 4 ints per tile
+// ints in one GEMM schedule: header, 4 per row tile, 2 per work item (row tile x column octet)
 static inline size_t tile_table_ints(const prism_layer_desc& d, int T) {
-  return align_up(4 + 4 * (size_t)max_tiles(d, T), 64);
+  const size_t A = (size_t)T * d.top_k;
+  const size_t mt = A / kMinTileM + d.n_experts + (size_t)d.n_shared * ceil_div(T > 0 ? T : 1, kMinTileM) + 1;
+  const int wide = d.ffn > d.hidden ? d.ffn : d.hidden;
+  const size_t nj8 = ceil_div(ceil_div(wide > 0 ? wide : 1, 64), 8);
+  return align_up(4 + 4 * mt + 2 * mt * nj8, 64);
 }
 
 static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
