@@ -145,7 +145,11 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
     return PRISM_OK;
   }
 
-  // bf16: schedules for the two GEMMs, then the GEMMs.
+  // bf16: schedules for the two GEMMs, then the GEMMs.  Buffer addressing uses
+  // 32-bit byte offsets, so every operand matrix must stay below 4 GiB.
+  if ((size_t)T * d.hidden * 2 >= (1ull << 32) || (size_t)rows * d.ffn * 2 >= (1ull << 32) ||
+      (size_t)d.ffn * d.hidden * 2 >= (1ull << 32))
+    return PRISM_ERR_UNSUPPORTED;
   using gg::GemmArgs;
   const size_t table_ints = tile_table_ints(d, T);
   int32_t* tiles1 = tiles;
@@ -163,10 +167,12 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
   g1.B0 = w.w_gate; g1.B1 = w.w_up; g1.SB0 = w.shared_w_gate; g1.SB1 = w.shared_w_up;
   g1.C = (uint16_t*)h;
   g1.tiles = tiles1; g1.local_src = local_src;
+  g1.a_bytes = (uint32_t)((size_t)T * d.hidden * 2);
+  g1.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g1.K = d.hidden; g1.N = d.ffn; g1.top_k = d.top_k; g1.E = d.n_experts;
   g1.n_ntiles = nt1;
   trace(stage_events, PRISM_STAGE_FFN_UP, 0, st);
-  PRISM_TRY((gg::launch_gemm<BM1, BN1, 2, 2, 32, 3, true>(g1, gg::max_row_tiles(d, T, BM1), st)));
+  PRISM_TRY((gg::launch_gemm<BM1, BN1, 2, 2, 32, 5, true>(g1, gg::max_row_tiles(d, T, BM1), st)));
   trace(stage_events, PRISM_STAGE_FFN_UP, 1, st);
 
   GemmArgs g2{};
@@ -174,10 +180,12 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
   g2.B0 = w.w_down; g2.B1 = nullptr; g2.SB0 = w.shared_w_down; g2.SB1 = nullptr;
   g2.C = (uint16_t*)y;
   g2.tiles = tiles2; g2.local_src = local_src;
+  g2.a_bytes = (uint32_t)((size_t)rows * d.ffn * 2);
+  g2.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g2.K = d.ffn; g2.N = d.hidden; g2.top_k = d.top_k; g2.E = d.n_experts;
   g2.n_ntiles = nt2;
   trace(stage_events, PRISM_STAGE_FFN_DOWN, 0, st);
-  PRISM_TRY((gg::launch_gemm<BM2, BN2, 2, 2, 64, 2, false>(g2, gg::max_row_tiles(d, T, BM2), st)));
+  PRISM_TRY((gg::launch_gemm<BM2, BN2, 2, 2, 32, 4, false>(g2, gg::max_row_tiles(d, T, BM2), st)));
   trace(stage_events, PRISM_STAGE_FFN_DOWN, 1, st);
   return PRISM_OK;
 }

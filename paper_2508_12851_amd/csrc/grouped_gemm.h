@@ -31,6 +31,10 @@
 
 #include "prism_internal.h"
 
+#ifndef PRISM_GG_DBG
+#define PRISM_GG_DBG 0   // timing experiments only: 1 no refill loads, 2 no operand reads, 3 no barrier
+#endif
+
 namespace prism {
 namespace gg {
 
@@ -113,6 +117,8 @@ struct GemmArgs {
   uint16_t* C;              // GATED: h [rows, N]; else y [rows, N]
   const int32_t* tiles;
   const int32_t* local_src;
+  uint32_t a_bytes;         // size of A in bytes (buffer range check), < 2^32
+  uint32_t b_bytes;         // size of one weight matrix in bytes, < 2^32
   int K;                    // contraction length (H for GEMM1, F for GEMM2)
   int N;                    // output columns (F for GEMM1, H for GEMM2)
   int top_k;
@@ -123,7 +129,7 @@ struct GemmArgs {
 constexpr int kGemmThreads = 256;
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef __attribute__((address_space(1))) const void* gbl_ptr_t;
+constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
 
 __device__ __forceinline__ float silu(float z) { return z / (1.0f + __expf(-z)); }
 
@@ -144,6 +150,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // BK contraction elements per LDS stage (32 or 64), STAGES stages in flight.
 template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED>
 __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmArgs p) {
+#if defined(__HIP_DEVICE_COMPILE__)   // buffer resources exist in device code only
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   static_assert(BK == 32 || BK == 64, "LDS rows are 64 or 128 bytes");
   constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -158,7 +165,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   constexpr int LPS = A_CH + B_CH;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int KK = BK / 16;                 // MFMA k-steps per stage
-  static_assert((STAGES - 2) * LPS <= 63, "vmcnt is a 6-bit counter");
+  static_assert((STAGES - 1) * LPS <= 63, "vmcnt is a 6-bit counter");
 
   extern __shared__ __align__(16) uint8_t smem[];
 
@@ -186,12 +193,19 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   // ---- global -> LDS assignment ------------------------------------------------
   // Wavefront w fills row groups w, w + 4, ...; a lane owns LDS slot lane % CPR of
   // row lane / CPR of the group and fetches the chunk that belongs in that slot.
-  // Addresses are a scalar base (matrix pointer + k offset) plus a per-lane 32-bit
-  // byte offset that never changes, so a load costs no vector ALU work.
   const int sub = lane / CPR;
   const int lrow = wave * RPG + sub;              // + 4 RPG i (>= 32 rows: does not change the key)
   const int c = (lane % CPR) ^ swizzle_key<BK>(lrow);   // global chunk fetched by this lane
-  const uint8_t* a_base = (const uint8_t*)p.A;
+  // Buffer resources (base, size for the hardware range check): loads are
+  // buffer_load_dwordx4 ... lds with a per-lane 32-bit byte offset that never
+  // changes and the k offset in a scalar register, so a load costs no vector ALU
+  // work and an out-of-range row can only read zeros.
+  const __amdgpu_buffer_rsrc_t a_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, (int)p.a_bytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t b0_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)b0, 0, (int)p.b_bytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t b1_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)(GATED ? b1 : b0), 0, (int)p.b_bytes, kBufferFlags);
   uint32_t a_voff[A_CH];
 #pragma unroll
   for (int i = 0; i < A_CH; ++i) {
@@ -201,7 +215,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     else src = (uint32_t)(row_start + rr);
     a_voff[i] = (src * (uint32_t)p.K + c * 8) * 2;
   }
-  const uint8_t* b_base[B_CH];
+  bool b_up[B_CH];
   uint32_t b_voff[B_CH];
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
@@ -209,36 +223,33 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     if (GATED) {
       // tile rows [w WN, w WN + WN/2) are gate rows, the next WN/2 the up rows of the same f
       const int w = g0 / WN, within = g0 % WN;
-      const bool up = within >= WN / 2;
+      b_up[i] = within >= WN / 2;
       const int f = min(nt * (BN / 2) + w * (WN / 2) + (within % (WN / 2)) + sub, p.N - 1);
-      b_base[i] = (const uint8_t*)(up ? b1 : b0);
       b_voff[i] = ((uint32_t)f * (uint32_t)p.K + c * 8) * 2;
     } else {
       const int n = min(nt * BN + g0 + sub, p.N - 1);
-      b_base[i] = (const uint8_t*)b0;
+      b_up[i] = false;
       b_voff[i] = ((uint32_t)n * (uint32_t)p.K + c * 8) * 2;
     }
   }
 
-  auto issue_loads = [&](int kt, int stage) {
+  // Issues loads [first, last) of the LPS loads that fill one stage with k-tile kt
+  // (A row groups first, then B row groups).
+  auto issue_loads = [&](int kt, int stage, int first, int last) {
     // wave-uniform LDS base of this wavefront's first row group; lane * 16 is implicit
     uint8_t* base = smem + stage * kStageBytes + wave * RPG * kRowBytes;
-    const size_t koff = (size_t)kt * (BK * 2);
-    // The empty asm keeps base + k offset in scalar registers (otherwise the
-    // compiler folds the lane offset in first and re-adds 64-bit vectors per load).
-    const uint8_t* ab = a_base + koff;
-    asm volatile("" : "+s"(ab));
+    const int koff = kt * (BK * 2);
 #pragma unroll
     for (int i = 0; i < A_CH; ++i)
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(ab + a_voff[i]),
-                                       (lds_ptr_t)(base + i * 4 * RPG * kRowBytes), 16, 0, 0);
+      if (i >= first && i < last)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)(base + i * 4 * RPG * kRowBytes),
+                                                 PRISM_GG_DBG == 7 ? 4 : 16, a_voff[i], koff, 0, 0);
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-      const uint8_t* bb = b_base[i] + koff;
-      asm volatile("" : "+s"(bb));
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t)(bb + b_voff[i]),
-                                       (lds_ptr_t)(base + (BM + i * 4 * RPG) * kRowBytes), 16, 0, 0);
-    }
+    for (int i = 0; i < B_CH; ++i)
+      if (A_CH + i >= first && A_CH + i < last)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_up[i] ? b1_rsrc : b0_rsrc,
+                                                 (lds_ptr_t)(base + (BM + i * 4 * RPG) * kRowBytes),
+                                                 PRISM_GG_DBG == 7 ? 4 : 16, b_voff[i], koff, 0, 0);
   };
 
   f32x16 acc[MI][NJ];
@@ -268,24 +279,46 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
       af[buf][i] = *reinterpret_cast<const bf16x8*>(base + a_off + i * 32 * kRowBytes + slot);
   };
 
-  // Ring protocol.  The prologue fills all STAGES stages with k-tiles 0..STAGES-1.
-  // While the last MFMA step of k-tile kt runs, the wavefront waits until k-tile
-  // kt + 1 has landed (only the STAGES - 2 younger tiles may still be in flight),
-  // meets the others at a barrier (so every wavefront holds its last operands of
-  // stage kt in registers), refills stage kt with k-tile kt + STAGES and reads the
-  // first operands of k-tile kt + 1.  Past the end the refill re-fetches the last
-  // k-tile into a stage nobody reads again, which keeps the vmcnt bookkeeping
-  // uniform.
+  // Ring protocol (STAGES >= 3).  The prologue fills stages 0..STAGES-2 with
+  // k-tiles 0..STAGES-2.  Iteration kt computes from stage kt % STAGES and, spread
+  // evenly over its MFMA steps, refills stage (kt - 1) % STAGES -- free since the
+  // barrier that ended iteration kt - 1 -- with k-tile kt + STAGES - 1.  In its last
+  // step the wavefront waits until k-tile kt + 1 has landed (vmcnt counts only the
+  // younger loads), drains its own LDS reads, meets the others at the barrier and
+  // reads the first operands of k-tile kt + 1.  The last part of the refill is issued
+  // after the barrier so that it, too, sits among MFMAs.  Past the end the refill
+  // re-fetches the last k-tile into a stage nobody reads again, which keeps the
+  // vmcnt bookkeeping uniform.
+  static_assert(STAGES >= 3, "ring needs a free stage to refill during an iteration");
+  static_assert(LPS % KK == 0, "loads per stage split evenly over the MFMA steps");
+  constexpr int kPart = LPS / KK;
   const int KT = p.K / BK;
 #pragma unroll
-  for (int s = 0; s < STAGES; ++s) issue_loads(min(s, KT - 1), s);
-  wait_vmcnt<(STAGES - 1) * LPS>();
+  for (int s = 0; s < STAGES - 1; ++s) issue_loads(min(s, KT - 1), s, 0, LPS);
+  wait_vmcnt<(STAGES - 2) * LPS>();
   __builtin_amdgcn_s_barrier();
   read_frags(0, 0, 0);
 
-  int stage = 0;
-  for (int kt = 0; kt < KT; ++kt) {
+#if PRISM_GG_DBG == 8
+  long long dbg_wait = 0, dbg_bar = 0;
+  const long long dbg_t0 = clock64();
+#endif
+  int stage = 0;                       // kt % STAGES
+  int fill_stage = STAGES - 1;         // (kt + STAGES - 1) % STAGES
+#if PRISM_GG_DBG >= 4
+  const int kt_end = KT * 8;
+#else
+  const int kt_end = KT;
+#endif
+  for (int kt = 0; kt < kt_end; ++kt) {
     const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
+#if PRISM_GG_DBG == 5 || PRISM_GG_DBG == 7
+    const int fill_kt = (kt + STAGES - 1) % KT;
+#elif PRISM_GG_DBG == 6
+    const int fill_kt = 0;
+#else
+    const int fill_kt = min(kt + STAGES - 1, KT - 1);
+#endif
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       constexpr int kReads = MI + NJ;
@@ -293,44 +326,55 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
       if (kk + 1 < KK) {
         read_frags(stage, kk + 1, (kk + 1) & 1);
       } else {
-        wait_vmcnt<(STAGES - 2) * LPS>();
+#if PRISM_GG_DBG == 8
+        const long long t0 = clock64();
+#endif
+        wait_vmcnt<(STAGES - 3) * LPS + (KK - 1) * kPart>();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#if PRISM_GG_DBG == 8
+        const long long t1 = clock64();
+#endif
         __builtin_amdgcn_s_barrier();
+#if PRISM_GG_DBG == 8
+        const long long t2 = clock64();
+        dbg_wait += t1 - t0; dbg_bar += t2 - t1;
+#endif
         read_frags(next_stage, 0, (kk + 1) & 1);
-        issue_loads(min(kt + STAGES, KT - 1), stage);
       }
+#if PRISM_GG_DBG != 1 && PRISM_GG_DBG != 4
+      issue_loads(fill_kt, fill_stage, kk * kPart, (kk + 1) * kPart);
+#endif
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
       // Issue order inside the step: one MFMA first (so the wait for this step's
-      // operands precedes any new LDS read), then the next step's operand reads
-      // one per MFMA, then the global->LDS refill spread over the remaining MFMAs.
+      // operands precedes any new LDS read), then the next step's operand reads one
+      // per MFMA, then this step's share of the refill one per MFMA.
       // (Tiles with too little matrix work per step are left to the compiler.)
-      if constexpr (kMfma >= kReads + 2) {
+      if constexpr (kMfma >= kReads + kPart + 1) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
 #pragma unroll
         for (int r = 0; r < kReads; ++r) {
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
-        if (kk + 1 == KK) {
-          constexpr int kRest = kMfma - 1 - kReads;
-          constexpr int kPer = (LPS + kRest - 1) / kRest;
 #pragma unroll
-          for (int r = 0; r < kRest; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x020, kPer, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          }
-        } else {
-          __builtin_amdgcn_sched_group_barrier(0x008, kMfma - 1 - kReads, 0);
+        for (int r = 0; r < kPart; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - 1 - kReads - kPart, 0);
       }
     }
     stage = next_stage;
+    fill_stage = fill_stage + 1 == STAGES ? 0 : fill_stage + 1;
   }
 
+#if PRISM_GG_DBG == 8
+  const long long dbg_t1 = clock64();
+#endif
   // ---- epilogue ---------------------------------------------------------------
   // Accumulator register v of lane (r32, q) is row 8 (v / 4) + 4 q + v % 4, column r32.
   if (GATED) {
@@ -366,6 +410,13 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
         }
       }
   }
+#if PRISM_GG_DBG == 8
+  if (lane == 0) {
+    long long* d = (long long*)p.local_src + 1024 * 1024 + ((size_t)blockIdx.x * 4 + wave) * 8;   // harness-provided scratch
+    d[0] = dbg_t1 - dbg_t0; d[1] = dbg_wait; d[2] = dbg_bar; d[3] = clock64() - dbg_t1; d[4] = dbg_t0; d[5] = KT;
+  }
+#endif
+#endif  // __HIP_DEVICE_COMPILE__
 }
 
 // Upper bound on the number of row tiles for T tokens (host side).
