@@ -112,7 +112,7 @@ prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
   Workspace ws;
   PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
   return launch_expert_ffn(*desc, x, *weights, local_src, local_offsets, T, y, ws.h, ws.tiles,
-                           (hipStream_t)stream, nullptr);
+                           ws.part, (hipStream_t)stream, nullptr);
 }
 
 prism_status prism_combine(const prism_layer_desc* desc, const void* y, const int32_t* local_src,
@@ -162,7 +162,7 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                             ws.block_hist, st));
   trace(ev, PRISM_STAGE_DISPATCH, 1, st);
   PRISM_TRY(launch_expert_ffn(*desc, x, *weights, ws.local_src, ws.local_offsets, T, ws.y, ws.h,
-                              ws.tiles, st, ev));
+                              ws.tiles, ws.part, st, ev));
   trace(ev, PRISM_STAGE_COMBINE, 0, st);
   PRISM_TRY(launch_combine(*desc, ws.y, ws.inv, topk_gate, T, out, st));
   trace(ev, PRISM_STAGE_COMBINE, 1, st);

@@ -118,12 +118,94 @@ __global__ __launch_bounds__(256) void ffn2_f32_kernel(const F32Args p) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// bf16 path: two grouped GEMMs on the matrix cores
+// ---------------------------------------------------------------------------
+template <int BM_, int BN_, int BK_, int STAGES_> struct TileCfg {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
+};
+
+// Sums the contraction slices of the split down projection: y = bf16(sum_s part[s]).
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part,
+                                                            const int32_t* __restrict__ local_offsets,
+                                                            int E, int A, int rows, int H, int n_splits,
+                                                            uint16_t* __restrict__ y) {
+  const int vec_per_row = H / 4;
+  const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long long)rows * vec_per_row) return;
+  const int row = (int)(gid / vec_per_row);
+  if (row >= local_offsets[E] && row < A) return;   // rows that hold no assignment
+  const int col = (int)(gid - (long long)row * vec_per_row) * 4;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < n_splits; ++s)
+    acc += *reinterpret_cast<const f32x4*>(part + ((size_t)s * rows + row) * H + col);
+  bf16x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[e];
+  *reinterpret_cast<bf16x4*>(y + (size_t)row * H + col) = o;
+}
+
+template <typename C1, typename C2, bool SPLIT_DOWN>
+prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_expert_weights& w,
+                          const int32_t* local_src, const int32_t* local_offsets, int T, void* y,
+                          void* h, int32_t* tiles, float* part, hipStream_t st,
+                          void* const* stage_events) {
+  using gg::GemmArgs;
+  const int A = T * d.top_k;
+  const int rows = A + d.n_shared * T;
+  int32_t* tiles1 = tiles;
+  int32_t* tiles2 = tiles + tile_table_ints(d, T);
+  const int nt1 = ceil_div(d.ffn, C1::BN / 2);     // GEMM1 tile: BN/2 gate rows + BN/2 up rows
+  const int nt2 = ceil_div(d.hidden, C2::BN);
+  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, C1::BM, nt1, tiles1, st));
+  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, C2::BM, nt2, tiles2, st));
+
+  GemmArgs g1{};
+  g1.A = (const uint16_t*)x;
+  g1.B0 = w.w_gate; g1.B1 = w.w_up; g1.SB0 = w.shared_w_gate; g1.SB1 = w.shared_w_up;
+  g1.C = (uint16_t*)h;
+  g1.tiles = tiles1; g1.local_src = local_src;
+  g1.a_bytes = (uint32_t)((size_t)T * d.hidden * 2);
+  g1.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
+  g1.K = d.hidden; g1.N = d.ffn; g1.top_k = d.top_k; g1.E = d.n_experts;
+  g1.n_ntiles = nt1;
+  trace(stage_events, PRISM_STAGE_FFN_UP, 0, st);
+  PRISM_TRY((gg::launch_gemm<C1::BM, C1::BN, 2, 2, C1::BK, C1::STAGES, true>(
+      g1, gg::max_row_tiles(d, T, C1::BM), st)));
+  trace(stage_events, PRISM_STAGE_FFN_UP, 1, st);
+
+  GemmArgs g2{};
+  g2.A = (const uint16_t*)h;
+  g2.B0 = w.w_down; g2.B1 = nullptr; g2.SB0 = w.shared_w_down; g2.SB1 = nullptr;
+  g2.C = (uint16_t*)y;
+  g2.Cpart = part; g2.c_rows = rows;
+  g2.tiles = tiles2; g2.local_src = local_src;
+  g2.a_bytes = (uint32_t)((size_t)rows * d.ffn * 2);
+  g2.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
+  g2.K = d.ffn; g2.N = d.hidden; g2.top_k = d.top_k; g2.E = d.n_experts;
+  g2.n_ntiles = nt2;
+  // every slice must own at least one k-tile, or its partial sums would stay unwritten
+  const int n_splits = SPLIT_DOWN ? (d.ffn / C2::BK < kDecodeSplits ? d.ffn / C2::BK : kDecodeSplits) : 1;
+  trace(stage_events, PRISM_STAGE_FFN_DOWN, 0, st);
+  PRISM_TRY((gg::launch_gemm<C2::BM, C2::BN, 2, 2, C2::BK, C2::STAGES, false, SPLIT_DOWN>(
+      g2, gg::max_row_tiles(d, T, C2::BM), st, n_splits)));
+  if (SPLIT_DOWN) {
+    const long long threads = (long long)rows * (d.hidden / 4);
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                       part, local_offsets, d.n_experts, A, rows, d.hidden, n_splits, (uint16_t*)y);
+    PRISM_CHECK_LAUNCH();
+  }
+  trace(stage_events, PRISM_STAGE_FFN_DOWN, 1, st);
+  return PRISM_OK;
+}
+
 }  // namespace
 
 prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
-                               int32_t* tiles, hipStream_t st, void* const* stage_events) {
+                               int32_t* tiles, float* part, hipStream_t st,
+                               void* const* stage_events) {
   if (T == 0) return PRISM_OK;
   const int A = T * d.top_k;
   const int rows = A + d.n_shared * T;
@@ -150,44 +232,16 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
   if ((size_t)T * d.hidden * 2 >= (1ull << 32) || (size_t)rows * d.ffn * 2 >= (1ull << 32) ||
       (size_t)d.ffn * d.hidden * 2 >= (1ull << 32))
     return PRISM_ERR_UNSUPPORTED;
-  using gg::GemmArgs;
-  const size_t table_ints = tile_table_ints(d, T);
-  int32_t* tiles1 = tiles;
-  int32_t* tiles2 = tiles + table_ints;
-
-  constexpr int BM1 = 256, BN1 = 256;      // GEMM1: 256 rows x (128 gate + 128 up) weight rows
-  constexpr int BM2 = 256, BN2 = 256;      // GEMM2: 256 rows x 256 output columns
-  const int nt1 = ceil_div(d.ffn, BN1 / 2);
-  const int nt2 = ceil_div(d.hidden, BN2);
-  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, BM1, nt1, tiles1, st));
-  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, BM2, nt2, tiles2, st));
-
-  GemmArgs g1{};
-  g1.A = (const uint16_t*)x;
-  g1.B0 = w.w_gate; g1.B1 = w.w_up; g1.SB0 = w.shared_w_gate; g1.SB1 = w.shared_w_up;
-  g1.C = (uint16_t*)h;
-  g1.tiles = tiles1; g1.local_src = local_src;
-  g1.a_bytes = (uint32_t)((size_t)T * d.hidden * 2);
-  g1.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
-  g1.K = d.hidden; g1.N = d.ffn; g1.top_k = d.top_k; g1.E = d.n_experts;
-  g1.n_ntiles = nt1;
-  trace(stage_events, PRISM_STAGE_FFN_UP, 0, st);
-  PRISM_TRY((gg::launch_gemm<BM1, BN1, 2, 2, 32, 5, true>(g1, gg::max_row_tiles(d, T, BM1), st)));
-  trace(stage_events, PRISM_STAGE_FFN_UP, 1, st);
-
-  GemmArgs g2{};
-  g2.A = (const uint16_t*)h;
-  g2.B0 = w.w_down; g2.B1 = nullptr; g2.SB0 = w.shared_w_down; g2.SB1 = nullptr;
-  g2.C = (uint16_t*)y;
-  g2.tiles = tiles2; g2.local_src = local_src;
-  g2.a_bytes = (uint32_t)((size_t)rows * d.ffn * 2);
-  g2.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
-  g2.K = d.ffn; g2.N = d.hidden; g2.top_k = d.top_k; g2.E = d.n_experts;
-  g2.n_ntiles = nt2;
-  trace(stage_events, PRISM_STAGE_FFN_DOWN, 0, st);
-  PRISM_TRY((gg::launch_gemm<BM2, BN2, 2, 2, 32, 4, false>(g2, gg::max_row_tiles(d, T, BM2), st)));
-  trace(stage_events, PRISM_STAGE_FFN_DOWN, 1, st);
-  return PRISM_OK;
+  if (T <= kDecodeMaxTokens) {
+    // Decode batch: every expert has at most 64 rows, the layer is bound by streaming
+    // the weights once.  Small tiles put ~1000 workgroups on the machine; the down
+    // projection also splits its contraction and a last kernel sums the slices.
+    return run_bf16_ffn<TileCfg<64, 128, 64, 4>, TileCfg<64, 128, 64, 4>, true>(
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
+  }
+  // Prefill batch: 256 x 256 tiles (GEMM1: 128 gate + 128 up weight rows).
+  return run_bf16_ffn<TileCfg<256, 256, 32, 5>, TileCfg<256, 256, 32, 4>, false>(
+      d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
 }
 
 }  // namespace prism

@@ -115,6 +115,8 @@ struct GemmArgs {
   const void* const* SB0;   // shared experts, same roles
   const void* const* SB1;
   uint16_t* C;              // GATED: h [rows, N]; else y [rows, N]
+  float* Cpart;             // SPLITK: [n_splits][c_rows][N] fp32 partial sums
+  int c_rows;               // rows of one partial-sum slice
   const int32_t* tiles;
   const int32_t* local_src;
   uint32_t a_bytes;         // size of A in bytes (buffer range check), < 2^32
@@ -148,7 +150,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // BM x BN output tile per workgroup; BN counts weight rows in the tile (for
 // GATED: BN/2 gate rows and BN/2 up rows).  Wavefronts form a WGM x WGN grid.
 // BK contraction elements per LDS stage (32 or 64), STAGES stages in flight.
-template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED>
+// SPLITK: blockIdx.y selects a slice of the contraction; the tile is written as
+// fp32 partial sums to p.Cpart[slice][row][col] (plain GEMM only).
+template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false>
 __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmArgs p) {
 #if defined(__HIP_DEVICE_COMPILE__)   // buffer resources exist in device code only
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
@@ -156,6 +160,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int MI = WM / 32, NJ = WN / 32;
   static_assert(MI >= 1 && NJ >= 1 && (!GATED || NJ % 2 == 0), "tile shape");
+  static_assert(!(GATED && SPLITK), "the gated epilogue needs complete sums");
   constexpr int kRowBytes = BK * 2;
   constexpr int CPR = BK / 8;                 // 16-byte chunks per LDS row
   constexpr int RPG = 1024 / kRowBytes;       // rows filled by one wavefront-wide 16-byte load
@@ -233,12 +238,19 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     }
   }
 
+  // this workgroup's slice of the contraction, in k-tiles
+  const int KT_all = p.K / BK;
+  const int kt_first = SPLITK ? (int)((long long)KT_all * blockIdx.y / gridDim.y) : 0;
+  const int kt_last = SPLITK ? (int)((long long)KT_all * (blockIdx.y + 1) / gridDim.y) : KT_all;
+  const int KT = kt_last - kt_first;
+  if (SPLITK && KT <= 0) return;
+
   // Issues loads [first, last) of the LPS loads that fill one stage with k-tile kt
   // (A row groups first, then B row groups).
   auto issue_loads = [&](int kt, int stage, int first, int last) {
     // wave-uniform LDS base of this wavefront's first row group; lane * 16 is implicit
     uint8_t* base = smem + stage * kStageBytes + wave * RPG * kRowBytes;
-    const int koff = kt * (BK * 2);
+    const int koff = (kt_first + kt) * (BK * 2);
 #pragma unroll
     for (int i = 0; i < A_CH; ++i)
       if (i >= first && i < last)
@@ -290,9 +302,8 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   // re-fetches the last k-tile into a stage nobody reads again, which keeps the
   // vmcnt bookkeeping uniform.
   static_assert(STAGES >= 3, "ring needs a free stage to refill during an iteration");
-  static_assert(LPS % KK == 0, "loads per stage split evenly over the MFMA steps");
-  constexpr int kPart = LPS / KK;
-  const int KT = p.K / BK;
+  constexpr int kPart = (LPS + KK - 1) / KK;     // most loads one step issues
+
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s) issue_loads(min(s, KT - 1), s, 0, LPS);
   wait_vmcnt<(STAGES - 2) * LPS>();
@@ -329,7 +340,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
 #if PRISM_GG_DBG == 8
         const long long t0 = clock64();
 #endif
-        wait_vmcnt<(STAGES - 3) * LPS + (KK - 1) * kPart>();
+        wait_vmcnt<(STAGES - 3) * LPS + (KK - 1) * LPS / KK>();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #if PRISM_GG_DBG == 8
         const long long t1 = clock64();
@@ -342,13 +353,13 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
         read_frags(next_stage, 0, (kk + 1) & 1);
       }
 #if PRISM_GG_DBG != 1 && PRISM_GG_DBG != 4
-      issue_loads(fill_kt, fill_stage, kk * kPart, (kk + 1) * kPart);
+      issue_loads(fill_kt, fill_stage, kk * LPS / KK, (kk + 1) * LPS / KK);
 #endif
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
       // Issue order inside the step: one MFMA first (so the wait for this step's
       // operands precedes any new LDS read), then the next step's operand reads one
       // per MFMA, then this step's share of the refill one per MFMA.
@@ -376,39 +387,50 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   const long long dbg_t1 = clock64();
 #endif
   // ---- epilogue ---------------------------------------------------------------
-  // Accumulator register v of lane (r32, q) is row 8 (v / 4) + 4 q + v % 4, column r32.
-  if (GATED) {
-    constexpr int NH = NJ / 2;
+  // The weight rows are the MFMA's first operand, so accumulator register v of
+  // lane (r32, q) is output row (activation row) r32 of subtile i and output
+  // column 8 (v / 4) + 4 q + v % 4 of subtile j: four consecutive columns per
+  // register quad, written as one 8-byte (bf16) or 16-byte (fp32 partial) store.
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+  for (int i = 0; i < MI; ++i) {
+    const int row = wm * WM + i * 32 + r32;
+    if (row >= row_count) continue;
+    const size_t crow = (size_t)(row_start + row);
+    if (GATED) {
+      constexpr int NH = NJ / 2;
 #pragma unroll
-      for (int j = 0; j < NH; ++j) {
-        const int f = nt * (BN / 2) + wn * (WN / 2) + j * 32 + r32;
+      for (int j = 0; j < NH; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = wm * WM + i * 32 + (v >> 2) * 8 + q * 4 + (v & 3);
-          if (row < row_count && f < p.N) {
-            const float hval = silu(acc[i][j][v]) * acc[i][j + NH][v];
-            const bf16_t hb = (bf16_t)hval;
-            p.C[(size_t)(row_start + row) * p.N + f] = *reinterpret_cast<const uint16_t*>(&hb);
+        for (int vg = 0; vg < 4; ++vg) {
+          const int f = nt * (BN / 2) + wn * (WN / 2) + j * 32 + vg * 8 + q * 4;
+          if (f < p.N) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              o[e] = (bf16_t)(silu(acc[i][j][vg * 4 + e]) * acc[i][j + NH][vg * 4 + e]);
+            *reinterpret_cast<bf16x4*>(p.C + crow * p.N + f) = o;
           }
         }
-      }
-  } else {
+    } else {
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+      for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        const int n = nt * BN + wn * WN + j * 32 + r32;
+        for (int vg = 0; vg < 4; ++vg) {
+          const int n = nt * BN + wn * WN + j * 32 + vg * 8 + q * 4;
+          if (n < p.N) {
+            if (SPLITK) {
+              const f32x4 o = {acc[i][j][vg * 4], acc[i][j][vg * 4 + 1], acc[i][j][vg * 4 + 2],
+                               acc[i][j][vg * 4 + 3]};
+              *reinterpret_cast<f32x4*>(p.Cpart + ((size_t)blockIdx.y * p.c_rows + crow) * p.N + n) = o;
+            } else {
+              bf16x4 o;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = wm * WM + i * 32 + (v >> 2) * 8 + q * 4 + (v & 3);
-          if (row < row_count && n < p.N) {
-            const bf16_t yb = (bf16_t)acc[i][j][v];
-            p.C[(size_t)(row_start + row) * p.N + n] = *reinterpret_cast<const uint16_t*>(&yb);
+              for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[i][j][vg * 4 + e];
+              *reinterpret_cast<bf16x4*>(p.C + crow * p.N + n) = o;
+            }
           }
         }
-      }
+    }
   }
 #if PRISM_GG_DBG == 8
   if (lane == 0) {
@@ -435,11 +457,11 @@ static inline prism_status launch_build_schedule(const prism_layer_desc& d,
   return PRISM_OK;
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED>
-prism_status launch_gemm(const GemmArgs& args, int max_mtiles, hipStream_t st) {
+template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false>
+prism_status launch_gemm(const GemmArgs& args, int max_mtiles, hipStream_t st, int n_splits = 1) {
   constexpr int smem = STAGES * (BM + BN) * BK * 2;
   static_assert(smem <= 160 * 1024, "LDS per workgroup");
-  auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED>;
+  auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -449,7 +471,8 @@ prism_status launch_gemm(const GemmArgs& args, int max_mtiles, hipStream_t st) {
   const long long blocks = (long long)max_mtiles * ceil_div(args.n_ntiles, kXcds) * kXcds;
   if (blocks <= 0) return PRISM_OK;
   if (blocks > 0x7fffffffLL) return PRISM_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kGemmThreads), smem, st, args);
+  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks, SPLITK ? n_splits : 1), dim3(kGemmThreads), smem,
+                     st, args);
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;
 }

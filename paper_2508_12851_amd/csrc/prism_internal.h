@@ -28,6 +28,8 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // prism_workspace_bytes() fits all of them.
 // ---------------------------------------------------------------------------
 constexpr int kDispatchChunk = 2048;   // assignments per dispatch block
+constexpr int kDecodeMaxTokens = 64;    // batches up to this size take the weight-streaming path
+constexpr int kDecodeSplits = 8;        // contraction slices of its down projection
 constexpr int kMinTileM = 64;           // smallest row tile of the grouped GEMM (bounds table sizes)
 
 struct Workspace {
@@ -38,6 +40,7 @@ struct Workspace {
   int32_t* tiles;          // 2 x [tile_table_ints]: schedules of the two grouped GEMMs
   void* h;                 // [(A + S*T) * F] layer dtype: silu(gate)*up
   void* y;                 // [(A + S*T) * H] layer dtype: expert outputs
+  float* part;             // decode batches only: [kDecodeSplits][A + S*T][H] fp32 partial sums
   size_t total;
 };
 
@@ -68,6 +71,8 @@ static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
   w.tiles = (int32_t*)take(2 * tile_table_ints(d, T) * 4);
   w.h = take(rows * d.ffn * es);
   w.y = take(rows * d.hidden * es);
+  w.part = (float*)take(d.dtype == PRISM_BF16 && T <= kDecodeMaxTokens
+                            ? (size_t)kDecodeSplits * rows * d.hidden * 4 : 0);
   w.total = off;
   return w;
 }
@@ -99,7 +104,8 @@ prism_status launch_dispatch(const prism_layer_desc& d, const int32_t* topk_idx,
 prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
-                               int32_t* tiles, hipStream_t st, void* const* stage_events);
+                               int32_t* tiles, float* part, hipStream_t st,
+                               void* const* stage_events);
 
 // Records stage_events[2 * stage + end] on st when tracing is on and the pair is set.
 static inline void trace(void* const* ev, int stage, int end, hipStream_t st) {

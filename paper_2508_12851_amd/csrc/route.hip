@@ -5,12 +5,14 @@
 // the dot products are accumulated in fp64 (every bf16*bf16 and fp32*fp32
 // product is exact in fp64) on the fp64 matrix cores and rounded once to fp32.
 //
-// Work split: a workgroup of 4 wavefronts takes 64 tokens, 16 per wavefront.
-// Each wavefront owns a 16-token x E logit tile as v_mfma_f64_16x16x4 blocks,
-// operands loaded straight from global memory with 16-byte (bf16) or 2x16-byte
-// (fp32) loads per lane: lane (r = lane % 16, q = lane / 16) fetches elements
-// h0 + 8q .. h0 + 8q + 7 of row r, and MFMA step j consumes element j of every
-// lane, so both operands see the same permutation of the contraction index.
+// Work split: a workgroup takes 16 tokens; its 8 wavefronts split the hidden
+// dimension (so even a 32-token decode batch has 16 wavefronts in flight) and
+// their partial 16-token x E logit tiles, held as v_mfma_f64_16x16x4 blocks, are
+// summed pairwise through LDS in a fixed order.  Operands are loaded straight
+// from global memory with 16-byte (bf16) or 2x16-byte (fp32) loads per lane:
+// lane (r = lane % 16, q = lane / 16) fetches elements h0 + 8q .. h0 + 8q + 7 of
+// row r, and MFMA step j consumes element j of every lane, so both operands see
+// the same permutation of the contraction index.
 // The accumulator layout leaves each token's logits spread over one 16-lane
 // group, so the k best experts are picked right there with xor-shuffle
 // arg-max reductions over (logit, index) pairs, four tokens at a time.
@@ -19,9 +21,8 @@
 namespace prism {
 namespace {
 
-constexpr int kTokPerWave = 16;
-constexpr int kWavesPerBlock = 4;
-constexpr int kTokPerBlock = kTokPerWave * kWavesPerBlock;
+constexpr int kTokPerBlock = 16;
+constexpr int kWavesPerBlock = 8;      // split the hidden dimension
 
 __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
   const f32x4 a = *reinterpret_cast<const f32x4*>(p);
@@ -44,12 +45,13 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
     unsigned long long* __restrict__ counts_accum) {
   constexpr int EP = NT * 16;             // padded expert count
   __shared__ int s_counts[EP];
+  extern __shared__ __align__(16) double s_part[];   // [kWavesPerBlock / 2][NT * 4][64]
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int r = lane & 15;
   const int q = lane >> 4;
-  const int tok0 = blockIdx.x * kTokPerBlock + wave * kTokPerWave;
+  const int tok0 = blockIdx.x * kTokPerBlock;
 
   for (int e = threadIdx.x; e < EP; e += blockDim.x) s_counts[e] = 0;
   __syncthreads();
@@ -65,7 +67,8 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
 #pragma unroll
   for (int n = 0; n < NT; ++n) wrow[n] = w_router + (size_t)min(n * 16 + r, E - 1) * H;
 
-  for (int h0 = 0; h0 < H; h0 += 32) {
+  // wavefront w takes the 32-element slices w, w + 8, w + 16, ... of the hidden dimension
+  for (int h0 = wave * 32; h0 < H; h0 += 32 * kWavesPerBlock) {
     // H % 8 == 0, so a lane's 8-element chunk is entirely inside or outside;
     // lanes past the end feed zeros (the MFMA itself is wave-wide).
     const int h = h0 + q * 8;
@@ -84,6 +87,29 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
         acc[n] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)wb[n][j], acc[n], 0, 0, 0);
     }
   }
+
+  // ---- sum the partial tiles: (1,3,5,7) -> (0,2,4,6), (2,6) -> (0,4), 4 -> 0 ----
+#pragma unroll
+  for (int step = 1; step < kWavesPerBlock; step <<= 1) {
+    const bool sender = (wave & (2 * step - 1)) == step;
+    const bool receiver = (wave & (2 * step - 1)) == 0;
+    double* slot = s_part + (size_t)(wave / (2 * step)) * (NT * 4 * 64);
+    if (sender) {
+#pragma unroll
+      for (int n = 0; n < NT; ++n)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) slot[(n * 4 + v) * 64 + lane] = acc[n][v];
+    }
+    __syncthreads();
+    if (receiver) {
+#pragma unroll
+      for (int n = 0; n < NT; ++n)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[n][v] += slot[(n * 4 + v) * 64 + lane];
+    }
+    __syncthreads();
+  }
+  if (wave != 0) return;   // wavefront 0 holds the full sums (no barrier follows)
 
   // ---- one rounding to fp32, then the fp32 bias add --------------------------
   // Accumulator register v of lane (r, q) is token 4v + q, expert 16n + r.
@@ -149,10 +175,10 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
       atomicAdd(&s_counts[myidx], 1);
     }
   }
-  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // this wavefront's LDS atomics, then its reads
 
   // ---- per-expert activation counts -----------------------------------------
-  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+  for (int e = lane; e < E; e += 64) {
     const int c = s_counts[e];
     if (c != 0) {
       atomicAdd(&counts[e], c);
@@ -173,8 +199,17 @@ prism_status launch_typed(const prism_layer_desc& d, const void* x, const void* 
   const int E = d.n_experts;
   const int nt = ceil_div(E, 16);
   const dim3 grid(ceil_div(T, kTokPerBlock)), block(kWavesPerBlock * kWave);
+  static bool attr_set = false;
+  if (!attr_set) {   // the 256-expert tile needs 128 KiB of LDS for the partial sums
+    if (hipFuncSetAttribute((const void*)route_kernel<TIn, 16>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (kWavesPerBlock / 2) * 16 * 4 * 64 * 8) != hipSuccess)
+      return PRISM_ERR_LAUNCH;
+    attr_set = true;
+  }
 #define PRISM_ROUTE_CASE(NT)                                                                     \
-  hipLaunchKernelGGL((route_kernel<TIn, NT>), grid, block, 0, st, (const TIn*)x, (const TIn*)w,  \
+  hipLaunchKernelGGL((route_kernel<TIn, NT>), grid, block,                                      \
+                     (size_t)(kWavesPerBlock / 2) * NT * 4 * 64 * 8, st, (const TIn*)x, (const TIn*)w,  \
                      bias, T, d.hidden, E, d.top_k, d.bias_group_tokens, logits, idx, gate,     \
                      counts, (unsigned long long*)accum)
   if (nt <= 1) PRISM_ROUTE_CASE(1);
