@@ -190,7 +190,7 @@ def main():
         "layer_tflops": layer_flop / (ms_per_step * 1e-3) / 1e12,
     }
     if not args.no_cpu_baseline:
-        n_sample = args.cpu_sample_tokens or (cfg.T if decode else 256)
+        n_sample = args.cpu_sample_tokens or (cfg.T if decode else 2048)
         result["cpu_baseline"] = cpu_baseline(inp, n_sample)
     print(json.dumps(result), flush=True)
 

@@ -195,7 +195,8 @@ prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const 
  * NULL.  For stage s, if stage_events[2s] and stage_events[2s+1] are both
  * non-NULL, the first is recorded on `stream` right before and the second
  * right after that stage's kernels: the router kernel, the three dispatch
- * kernels, the gate/up grouped GEMM alone, the down grouped GEMM alone, the
+ * kernels, the gate/up grouped GEMM alone, the down grouped GEMM (with, for
+ * decode-sized batches, the kernel that sums its contraction slices), the
  * combine kernel.  Nothing else differs from prism_moe_layer, which is this
  * call with stage_events == NULL.
  */

@@ -31,9 +31,6 @@
 
 #include "prism_internal.h"
 
-#ifndef PRISM_GG_DBG
-#define PRISM_GG_DBG 0   // timing experiments only: 1 no refill loads, 2 no operand reads, 3 no barrier
-#endif
 
 namespace prism {
 namespace gg {
@@ -255,13 +252,13 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     for (int i = 0; i < A_CH; ++i)
       if (i >= first && i < last)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)(base + i * 4 * RPG * kRowBytes),
-                                                 PRISM_GG_DBG == 7 ? 4 : 16, a_voff[i], koff, 0, 0);
+                                                 16, a_voff[i], koff, 0, 0);
 #pragma unroll
     for (int i = 0; i < B_CH; ++i)
       if (A_CH + i >= first && A_CH + i < last)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(b_up[i] ? b1_rsrc : b0_rsrc,
                                                  (lds_ptr_t)(base + (BM + i * 4 * RPG) * kRowBytes),
-                                                 PRISM_GG_DBG == 7 ? 4 : 16, b_voff[i], koff, 0, 0);
+                                                 16, b_voff[i], koff, 0, 0);
   };
 
   f32x16 acc[MI][NJ];
@@ -310,26 +307,11 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   __builtin_amdgcn_s_barrier();
   read_frags(0, 0, 0);
 
-#if PRISM_GG_DBG == 8
-  long long dbg_wait = 0, dbg_bar = 0;
-  const long long dbg_t0 = clock64();
-#endif
   int stage = 0;                       // kt % STAGES
   int fill_stage = STAGES - 1;         // (kt + STAGES - 1) % STAGES
-#if PRISM_GG_DBG >= 4
-  const int kt_end = KT * 8;
-#else
-  const int kt_end = KT;
-#endif
-  for (int kt = 0; kt < kt_end; ++kt) {
+  for (int kt = 0; kt < KT; ++kt) {
     const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
-#if PRISM_GG_DBG == 5 || PRISM_GG_DBG == 7
-    const int fill_kt = (kt + STAGES - 1) % KT;
-#elif PRISM_GG_DBG == 6
-    const int fill_kt = 0;
-#else
     const int fill_kt = min(kt + STAGES - 1, KT - 1);
-#endif
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       constexpr int kReads = MI + NJ;
@@ -337,24 +319,12 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
       if (kk + 1 < KK) {
         read_frags(stage, kk + 1, (kk + 1) & 1);
       } else {
-#if PRISM_GG_DBG == 8
-        const long long t0 = clock64();
-#endif
         wait_vmcnt<(STAGES - 3) * LPS + (KK - 1) * LPS / KK>();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#if PRISM_GG_DBG == 8
-        const long long t1 = clock64();
-#endif
         __builtin_amdgcn_s_barrier();
-#if PRISM_GG_DBG == 8
-        const long long t2 = clock64();
-        dbg_wait += t1 - t0; dbg_bar += t2 - t1;
-#endif
         read_frags(next_stage, 0, (kk + 1) & 1);
       }
-#if PRISM_GG_DBG != 1 && PRISM_GG_DBG != 4
       issue_loads(fill_kt, fill_stage, kk * LPS / KK, (kk + 1) * LPS / KK);
-#endif
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -383,9 +353,6 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     fill_stage = fill_stage + 1 == STAGES ? 0 : fill_stage + 1;
   }
 
-#if PRISM_GG_DBG == 8
-  const long long dbg_t1 = clock64();
-#endif
   // ---- epilogue ---------------------------------------------------------------
   // The weight rows are the MFMA's first operand, so accumulator register v of
   // lane (r32, q) is output row (activation row) r32 of subtile i and output
@@ -432,12 +399,6 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
         }
     }
   }
-#if PRISM_GG_DBG == 8
-  if (lane == 0) {
-    long long* d = (long long*)p.local_src + 1024 * 1024 + ((size_t)blockIdx.x * 4 + wave) * 8;   // harness-provided scratch
-    d[0] = dbg_t1 - dbg_t0; d[1] = dbg_wait; d[2] = dbg_bar; d[3] = clock64() - dbg_t1; d[4] = dbg_t0; d[5] = KT;
-  }
-#endif
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
