@@ -153,25 +153,27 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   using gg::GemmArgs;
   const int A = T * d.top_k;
   const int rows = A + d.n_shared * T;
-  int32_t* tiles1 = tiles;
-  int32_t* tiles2 = tiles + tile_table_ints(d, T);
+  // the k-tile ring of a workgroup must not be longer than its contraction slice
+  if (d.hidden / C1::BK < C1::STAGES - 1 || d.ffn / C2::BK < C2::STAGES - 1) return PRISM_ERR_UNSUPPORTED;
+  int32_t* sched1 = tiles;
+  int32_t* sched2 = tiles + tile_table_ints(d, T);
   const int nt1 = ceil_div(d.ffn, C1::BN / 2);     // GEMM1 tile: BN/2 gate rows + BN/2 up rows
   const int nt2 = ceil_div(d.hidden, C2::BN);
-  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, C1::BM, nt1, tiles1, st));
-  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, C2::BM, nt2, tiles2, st));
+  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, C1::BM, nt1, sched1, st));
+  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, C2::BM, nt2, sched2, st));
 
   GemmArgs g1{};
   g1.A = (const uint16_t*)x;
   g1.B0 = w.w_gate; g1.B1 = w.w_up; g1.SB0 = w.shared_w_gate; g1.SB1 = w.shared_w_up;
   g1.C = (uint16_t*)h;
-  g1.tiles = tiles1; g1.local_src = local_src;
+  g1.sched = sched1; g1.local_src = local_src;
+  g1.src_bytes = (uint32_t)A * 4;
   g1.a_bytes = (uint32_t)((size_t)T * d.hidden * 2);
   g1.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g1.K = d.hidden; g1.N = d.ffn; g1.top_k = d.top_k; g1.E = d.n_experts;
-  g1.n_ntiles = nt1;
   trace(stage_events, PRISM_STAGE_FFN_UP, 0, st);
   PRISM_TRY((gg::launch_gemm<C1::BM, C1::BN, 2, 2, C1::BK, C1::STAGES, true>(
-      g1, gg::max_row_tiles(d, T, C1::BM), st)));
+      g1, gg::sched_capacity(d, T, C1::BM, nt1), st)));
   trace(stage_events, PRISM_STAGE_FFN_UP, 1, st);
 
   GemmArgs g2{};
@@ -179,16 +181,19 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   g2.B0 = w.w_down; g2.B1 = nullptr; g2.SB0 = w.shared_w_down; g2.SB1 = nullptr;
   g2.C = (uint16_t*)y;
   g2.Cpart = part; g2.c_rows = rows;
-  g2.tiles = tiles2; g2.local_src = local_src;
+  g2.sched = sched2; g2.local_src = local_src;
   g2.a_bytes = (uint32_t)((size_t)rows * d.ffn * 2);
   g2.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g2.K = d.ffn; g2.N = d.hidden; g2.top_k = d.top_k; g2.E = d.n_experts;
-  g2.n_ntiles = nt2;
-  // every slice must own at least one k-tile, or its partial sums would stay unwritten
-  const int n_splits = SPLIT_DOWN ? (d.ffn / C2::BK < kDecodeSplits ? d.ffn / C2::BK : kDecodeSplits) : 1;
+  // every contraction slice must be at least as long as the k-tile ring
+  int n_splits = 1;
+  if (SPLIT_DOWN) {
+    n_splits = (d.ffn / C2::BK) / (C2::STAGES - 1);
+    if (n_splits > kDecodeSplits) n_splits = kDecodeSplits;
+  }
   trace(stage_events, PRISM_STAGE_FFN_DOWN, 0, st);
   PRISM_TRY((gg::launch_gemm<C2::BM, C2::BN, 2, 2, C2::BK, C2::STAGES, false, SPLIT_DOWN>(
-      g2, gg::max_row_tiles(d, T, C2::BM), st, n_splits)));
+      g2, gg::sched_capacity(d, T, C2::BM, nt2), st, n_splits)));
   if (SPLIT_DOWN) {
     const long long threads = (long long)rows * (d.hidden / 4);
     hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
@@ -236,11 +241,18 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
     // Decode batch: every expert has at most 64 rows, the layer is bound by streaming
     // the weights once.  Small tiles put ~1000 workgroups on the machine; the down
     // projection also splits its contraction and a last kernel sums the slices.
-    return run_bf16_ffn<TileCfg<64, 128, 64, 4>, TileCfg<64, 128, 64, 4>, true>(
+    if (d.hidden >= 192 && d.ffn >= 192)
+      return run_bf16_ffn<TileCfg<64, 128, 64, 4>, TileCfg<64, 128, 64, 4>, true>(
+          d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
+    return run_bf16_ffn<TileCfg<64, 128, 32, 3>, TileCfg<64, 128, 32, 3>, true>(
         d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
   }
-  // Prefill batch: 256 x 256 tiles (GEMM1: 128 gate + 128 up weight rows).
-  return run_bf16_ffn<TileCfg<256, 256, 32, 5>, TileCfg<256, 256, 32, 4>, false>(
+  // Prefill batch: 256 x 256 tiles (GEMM1: 128 gate + 128 up weight rows).  Very short
+  // contractions (H or F of 64) get the shallowest ring.
+  if (d.hidden >= 128 && d.ffn >= 128)
+    return run_bf16_ffn<TileCfg<256, 256, 32, 4>, TileCfg<256, 256, 32, 4>, false>(
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
+  return run_bf16_ffn<TileCfg<256, 256, 32, 3>, TileCfg<256, 256, 32, 3>, false>(
       d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
 }
 

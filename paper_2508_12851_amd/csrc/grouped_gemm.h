@@ -4,52 +4,62 @@
 //   GATED   h[r, f] = silu( x[tok(r)] . W_gate^g[f] ) * ( x[tok(r)] . W_up^g[f] )
 //   plain   y[r, n] = h[r] . W_down^g[n]
 //
-// Rows are grouped by expert g; a device-built schedule (tile table + work
-// list) gives every workgroup its (row tile, column tile), so the host never
-// needs the routing-dependent segment sizes.
+// Rows are grouped by expert g; a device-built schedule gives every workgroup its
+// (row tile, column tile) items, so the host never needs the routing-dependent
+// segment sizes.
 //
 // Kernel shape: BM x BN output tile per workgroup of 4 wavefronts (WGM x WGN),
-// v_mfma_f32_32x32x16_bf16, operand tiles of 64 contraction elements staged in
+// v_mfma_f32_32x32x16_bf16, operand tiles of BK contraction elements staged in
 // LDS in a ring of STAGES stages.  An LDS row holds BK contraction elements
 // (128 or 64 bytes) as 16-byte chunks; chunk c of row r sits in slot
 // c ^ key(r) (key = (r >> 1) & 7 for 128-byte rows, (r >> 2) & 3 for 64-byte
 // rows), so the 16-byte operand reads of 16 consecutive rows hit 16 different
-// slots of the 256-byte bank window.  Stages are filled by global_load_lds_dwordx4 (no
-// VGPR staging): one instruction fills 1 KiB, and because each lane's LDS slot
-// is fixed (lane * 16 bytes), the swizzle is applied to the global chunk a
-// lane fetches instead.  Stage k is awaited with s_waitcnt vmcnt(n), n = the
-// loads of the younger stages, then one s_barrier per stage orders the ring.
+// slots of the 256-byte bank window.  Stages are filled by buffer_load_dwordx4
+// ... lds (no VGPR staging): one instruction fills 1 KiB, and because each
+// lane's LDS slot is fixed (lane * 16 bytes), the swizzle is applied to the
+// global chunk a lane fetches instead.  A stage is awaited with s_waitcnt
+// vmcnt(n), n = the loads of the younger stages, then one s_barrier per stage
+// orders the ring.
+//
+// The kernel is persistent: a workgroup walks its list of items, and the ring
+// keeps running across items -- while the last k-tiles of one item are being
+// multiplied, the first k-tiles of the next are already being fetched, and they
+// land while the epilogue of the first stores its results.
 //
 // Work order: the hardware hands consecutive workgroup ids to the 8 XCDs in
-// turn, each with a private L2.  Workgroup b therefore takes column tile
-// 8 j + (b % 8) of work item b / 8, and the work list walks, per expert, its
-// row tiles fastest: the ~32 workgroups resident on one XCD share a few weight
-// tiles and one expert's activation tiles, and every weight tile is fetched
-// into exactly one L2.
+// turn, each with a private L2.  Every (expert, column tile) pair is owned by
+// one XCD (pairs are dealt round-robin, so the XCDs stay balanced), and an
+// XCD's list walks its pairs with the row tiles fastest: the workgroups
+// resident on one XCD share a few weight tiles and one expert's activation
+// tiles, and every weight tile is fetched into exactly one L2.
 #ifndef PRISM_GROUPED_GEMM_H_
 #define PRISM_GROUPED_GEMM_H_
 
 #include "prism_internal.h"
-
 
 namespace prism {
 namespace gg {
 
 constexpr int kMaxGroups = PRISM_MAX_EXPERTS + PRISM_MAX_SHARED;
 constexpr int kXcds = 8;
+constexpr int kSchedHeader = 16;     // ints
+constexpr int kItemInts = 8;         // ints per work item
 
-// Schedule memory (int32): [0] n_mtiles, [1] n_work, [2] sched offset (ints), [3] unused,
-// then 4 ints per row tile:
-//   [0] group id g (g < E: routed expert g; else shared expert g - E)
-//   [1] first row of the tile in h / y row space
-//   [2] rows in the tile (1..BM)
-//   [3] first token of the tile for shared experts, -1 for routed ones
-// then 2 ints per work item: (row tile index, column-tile octet j).
+// Schedule memory (int32):
+//   [0] n_mtiles  [1] capacity of one XCD list (items)  [4 + x] items in the list of XCD x
+//   then, from int kSchedHeader on, 8 lists of `capacity` items of 8 ints:
+//     [0] group id g (g < E: routed expert g; else shared expert g - E)
+//     [1] first row of the row tile in h / y row space
+//     [2] rows in the tile (1..BM)
+//     [3] first token of the tile for shared experts, -1 for routed ones
+//     [4] column tile
 __global__ __launch_bounds__(512) void build_schedule_kernel(
-    const int32_t* __restrict__ local_offsets, int E, int S, int T, int A_total, int BM, int nj8,
-    int max_mtiles, int32_t* __restrict__ tiles) {
-  __shared__ int s_start[kMaxGroups + 1];
+    const int32_t* __restrict__ local_offsets, int E, int S, int T, int A_total, int BM,
+    int n_ntiles, int capacity, int32_t* __restrict__ sched) {
+  __shared__ int s_start[kMaxGroups + 1];            // first row tile of group g
   __shared__ int s_rows[kMaxGroups], s_row0[kMaxGroups];
+  __shared__ int s_rank[kMaxGroups];                 // index of g among the non-empty groups
+  __shared__ int s_base[kXcds][kMaxGroups + 1];      // items of XCD x before group g
   const int G = E + S;
   for (int g = threadIdx.x; g < G; g += blockDim.x) {
     int rows, row0;
@@ -65,15 +75,37 @@ __global__ __launch_bounds__(512) void build_schedule_kernel(
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    int run = 0;
+    int run = 0, rank = 0;
     for (int g = 0; g < G; ++g) {
       s_start[g] = run;
-      run += (s_rows[g] + BM - 1) / BM;
+      s_rank[g] = rank;
+      const int m = (s_rows[g] + BM - 1) / BM;
+      run += m;
+      rank += m > 0;
     }
     s_start[G] = run;
-    tiles[0] = run;
-    tiles[1] = run * nj8;
-    tiles[2] = 4 + 4 * max_mtiles;
+    sched[0] = run;
+    sched[1] = capacity;
+  }
+  __syncthreads();
+  // Pair (g, nt) has index q = rank(g) * n_ntiles + nt and belongs to XCD q % 8.
+  // XCD x owns the column tiles r, r + 8, ... of group g with r = (x - rank(g) n_ntiles) mod 8.
+  auto first_nt = [&](int g, int x) {
+    const int r = (x - s_rank[g] * n_ntiles) % kXcds;
+    return r < 0 ? r + kXcds : r;
+  };
+  if (threadIdx.x < kXcds) {
+    const int x = threadIdx.x;
+    int run = 0;
+    for (int g = 0; g < G; ++g) {
+      s_base[x][g] = run;
+      const int m = s_start[g + 1] - s_start[g];
+      const int r = first_nt(g, x);
+      const int c = r < n_ntiles ? (n_ntiles - 1 - r) / kXcds + 1 : 0;
+      run += m * c;
+    }
+    s_base[x][G] = run;
+    sched[4 + x] = run;
   }
   __syncthreads();
   const int n_mtiles = s_start[G];
@@ -85,23 +117,21 @@ __global__ __launch_bounds__(512) void build_schedule_kernel(
     }
     return lo;
   };
-  for (int i = threadIdx.x; i < n_mtiles; i += blockDim.x) {
+  const long long n_items = (long long)n_mtiles * n_ntiles;
+  for (long long w = threadIdx.x; w < n_items; w += blockDim.x) {
+    const int i = (int)(w % n_mtiles), nt = (int)(w / n_mtiles);
     const int g = group_of_tile(i);
     const int mi = i - s_start[g];
-    int32_t* out = tiles + 4 + 4 * i;
+    const int m = s_start[g + 1] - s_start[g];
+    const int x = (s_rank[g] * n_ntiles + nt) % kXcds;
+    const int pos = s_base[x][g] + ((nt - first_nt(g, x)) / kXcds) * m + mi;   // row tiles fastest
+    int32_t* out = sched + kSchedHeader + ((size_t)x * capacity + pos) * kItemInts;
     out[0] = g;
     out[1] = s_row0[g] + mi * BM;
     out[2] = min(BM, s_rows[g] - mi * BM);
     out[3] = g < E ? -1 : mi * BM;
-  }
-  int32_t* sched = tiles + 4 + 4 * max_mtiles;
-  const int n_work = n_mtiles * nj8;
-  for (int w = threadIdx.x; w < n_work; w += blockDim.x) {
-    const int g = group_of_tile(w / nj8);          // work of group g starts at s_start[g] * nj8
-    const int mg = s_start[g + 1] - s_start[g];
-    const int local = w - s_start[g] * nj8;
-    sched[2 * w + 0] = s_start[g] + local % mg;    // row tiles fastest
-    sched[2 * w + 1] = local / mg;
+    out[4] = nt;
+    out[5] = 0; out[6] = 0; out[7] = 0;
   }
 }
 
@@ -114,20 +144,26 @@ struct GemmArgs {
   uint16_t* C;              // GATED: h [rows, N]; else y [rows, N]
   float* Cpart;             // SPLITK: [n_splits][c_rows][N] fp32 partial sums
   int c_rows;               // rows of one partial-sum slice
-  const int32_t* tiles;
+  const int32_t* sched;
   const int32_t* local_src;
+  uint32_t src_bytes;       // size of local_src in bytes (T * k * 4)
   uint32_t a_bytes;         // size of A in bytes (buffer range check), < 2^32
   uint32_t b_bytes;         // size of one weight matrix in bytes, < 2^32
   int K;                    // contraction length (H for GEMM1, F for GEMM2)
   int N;                    // output columns (F for GEMM1, H for GEMM2)
   int top_k;
   int E;
-  int n_ntiles;
 };
 
 constexpr int kGemmThreads = 256;
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
+// Schedule entries and pointer tables are written before the kernel starts and
+// never during it; reading them through the constant address space lets the
+// compiler use scalar loads, which the vector-memory counter does not see.
+typedef const __attribute__((address_space(4))) int4* const_int4_ptr;
+typedef const __attribute__((address_space(4))) int32_t* const_int_ptr;
+typedef const void* const __attribute__((address_space(4)))* const_ptr_table;
 constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
 
 __device__ __forceinline__ float silu(float z) { return z / (1.0f + __expf(-z)); }
@@ -167,24 +203,20 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   constexpr int LPS = A_CH + B_CH;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int KK = BK / 16;                 // MFMA k-steps per stage
+  static_assert(STAGES >= 3, "ring needs a free stage to refill during an iteration");
   static_assert((STAGES - 1) * LPS <= 63, "vmcnt is a 6-bit counter");
 
   extern __shared__ __align__(16) uint8_t smem[];
 
-  const int n_work = p.tiles[1];
+  // ---- this workgroup's items: slot, slot + slots, ... of its XCD's list -----------
   const int xcd = blockIdx.x % kXcds;
-  const int item = blockIdx.x / kXcds;
-  if (item >= n_work) return;
-  const int32_t* sched = p.tiles + p.tiles[2];
-  const int mt = sched[2 * item];
-  const int nt = sched[2 * item + 1] * kXcds + xcd;
-  if (nt >= p.n_ntiles) return;
-  const int4 tile = *reinterpret_cast<const int4*>(p.tiles + 4 + 4 * mt);
-  const int g = tile.x, row_start = tile.y, row_count = tile.z, tok_base = tile.w;
-
-  const uint16_t* b0 = (const uint16_t*)(g < p.E ? p.B0[g] : p.SB0[g - p.E]);
-  const uint16_t* b1 = nullptr;
-  if (GATED) b1 = (const uint16_t*)(g < p.E ? p.B1[g] : p.SB1[g - p.E]);
+  const int slot = blockIdx.x / kXcds;
+  const int slots = gridDim.x / kXcds;
+  const const_int_ptr sched_c = (const_int_ptr)p.sched;
+  const int count = sched_c[4 + xcd];
+  if (slot >= count) return;
+  const const_int4_ptr items =
+      (const_int4_ptr)(p.sched + kSchedHeader) + (size_t)xcd * sched_c[1] * (kItemInts / 4);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -192,82 +224,125 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   const int wm = wave / WGN, wn = wave % WGN;
   const int r32 = lane & 31, q = lane >> 5;
 
-  // ---- global -> LDS assignment ------------------------------------------------
-  // Wavefront w fills row groups w, w + 4, ...; a lane owns LDS slot lane % CPR of
-  // row lane / CPR of the group and fetches the chunk that belongs in that slot.
-  const int sub = lane / CPR;
-  const int lrow = wave * RPG + sub;              // + 4 RPG i (>= 32 rows: does not change the key)
-  const int c = (lane % CPR) ^ swizzle_key<BK>(lrow);   // global chunk fetched by this lane
-  // Buffer resources (base, size for the hardware range check): loads are
-  // buffer_load_dwordx4 ... lds with a per-lane 32-bit byte offset that never
-  // changes and the k offset in a scalar register, so a load costs no vector ALU
-  // work and an out-of-range row can only read zeros.
-  const __amdgpu_buffer_rsrc_t a_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, (int)p.a_bytes, kBufferFlags);
-  const __amdgpu_buffer_rsrc_t b0_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc((void*)b0, 0, (int)p.b_bytes, kBufferFlags);
-  const __amdgpu_buffer_rsrc_t b1_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc((void*)(GATED ? b1 : b0), 0, (int)p.b_bytes, kBufferFlags);
-  uint32_t a_voff[A_CH];
-#pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    const int rr = min(lrow + 4 * RPG * i, row_count - 1);
-    uint32_t src;
-    if (GATED) src = tok_base >= 0 ? (uint32_t)(tok_base + rr) : (uint32_t)(p.local_src[row_start + rr] / p.top_k);
-    else src = (uint32_t)(row_start + rr);
-    a_voff[i] = (src * (uint32_t)p.K + c * 8) * 2;
-  }
-  bool b_up[B_CH];
-  uint32_t b_voff[B_CH];
-#pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    const int g0 = wave * RPG + 4 * RPG * i;      // first tile row of the group (scalar)
-    if (GATED) {
-      // tile rows [w WN, w WN + WN/2) are gate rows, the next WN/2 the up rows of the same f
-      const int w = g0 / WN, within = g0 % WN;
-      b_up[i] = within >= WN / 2;
-      const int f = min(nt * (BN / 2) + w * (WN / 2) + (within % (WN / 2)) + sub, p.N - 1);
-      b_voff[i] = ((uint32_t)f * (uint32_t)p.K + c * 8) * 2;
-    } else {
-      const int n = min(nt * BN + g0 + sub, p.N - 1);
-      b_up[i] = false;
-      b_voff[i] = ((uint32_t)n * (uint32_t)p.K + c * 8) * 2;
-    }
-  }
-
   // this workgroup's slice of the contraction, in k-tiles
   const int KT_all = p.K / BK;
   const int kt_first = SPLITK ? (int)((long long)KT_all * blockIdx.y / gridDim.y) : 0;
   const int kt_last = SPLITK ? (int)((long long)KT_all * (blockIdx.y + 1) / gridDim.y) : KT_all;
   const int KT = kt_last - kt_first;
-  if (SPLITK && KT <= 0) return;
+  if (KT <= 0) return;
+
+  // ---- global -> LDS assignment ------------------------------------------------
+  // Wavefront w fills row groups w, w + 4, ...; a lane owns LDS slot lane % CPR of
+  // row lane / CPR of the group and fetches the chunk that belongs in that slot.
+  // Loads are buffer_load_dwordx4 ... lds with a per-lane 32-bit byte offset that
+  // never changes within an item and the k offset in a scalar register, so a load
+  // costs no vector ALU work; the buffer size makes an out-of-range row read zeros.
+  const int sub = lane / CPR;
+  const int lrow = wave * RPG + sub;              // + 4 RPG i (>= 32 rows: does not change the key)
+  const int c = (lane % CPR) ^ swizzle_key<BK>(lrow);   // global chunk fetched by this lane
+  const __amdgpu_buffer_rsrc_t a_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, (int)p.a_bytes, kBufferFlags);
+
+  // Item header as stored in the schedule.
+  struct Item {
+    int g, row_start, row_count, tok_base, nt;
+  };
+  // What the loads and the epilogue of an item need.
+  struct Ctx {
+    int row_start, row_count, nt;
+    const void* b0;
+    const void* b1;
+    uint32_t a_voff[A_CH];
+    uint32_t b_voff[B_CH];
+  };
+  auto fetch_item = [&](int idx) {   // idx is clamped: the result is only used when idx < count
+    const int i = min(idx, count - 1);
+    const int4 h0 = items[2 * i];
+    const int4 h1 = items[2 * i + 1];
+    return Item{h0.x, h0.y, h0.z, h0.w, h1.x};
+  };
+  // Second hop: expert pointers (scalar loads) and, for the gathered GEMM, the
+  // source rows of the row tile: each wavefront pulls the tile's BM entries of
+  // local_src into its own 1 KiB of LDS with one buffer_load ... lds (so the load is
+  // counted like the ring's loads and no VGPR waits on it), and reads its lanes'
+  // entries from there once the load has surely landed.
+  struct Raw {
+    const void* b0;
+    const void* b1;
+  };
+  static_assert(!GATED || BM <= 256, "one 1 KiB load brings the source rows of a row tile");
+  uint8_t* const src_lds = smem + STAGES * kStageBytes + wave * 1024;
+  const __amdgpu_buffer_rsrc_t src_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.local_src, 0, (int)p.src_bytes, kBufferFlags);
+  auto fetch_raw = [&](const Item& it) {
+    Raw r;
+    const const_ptr_table t0 = (const_ptr_table)(it.g < p.E ? p.B0 : p.SB0);
+    const const_ptr_table t1 = (const_ptr_table)(GATED ? (it.g < p.E ? p.B1 : p.SB1) : (it.g < p.E ? p.B0 : p.SB0));
+    const int gi = it.g < p.E ? it.g : it.g - p.E;
+    r.b0 = t0[gi];
+    r.b1 = t1[gi];
+    if (GATED)   // entry j of the LDS slot = local_src[row_start + j]; past the end reads 0
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsrc, (lds_ptr_t)src_lds, 16, lane * 16,
+                                               it.row_start * 4, 0, 0);
+    return r;
+  };
+  auto make_ctx = [&](const Item& it, const Raw& raw) {
+    Ctx cx;
+    cx.row_start = it.row_start; cx.row_count = it.row_count; cx.nt = it.nt;
+    cx.b0 = raw.b0; cx.b1 = raw.b1;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+      const int rr = min(lrow + 4 * RPG * i, it.row_count - 1);
+      uint32_t src;
+      if (GATED) {
+        const int a = reinterpret_cast<const int*>(src_lds)[rr];
+        src = it.tok_base >= 0 ? (uint32_t)(it.tok_base + rr) : (uint32_t)(a / p.top_k);
+      } else {
+        src = (uint32_t)(it.row_start + rr);
+      }
+      cx.a_voff[i] = (src * (uint32_t)p.K + c * 8) * 2;
+    }
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) {
+      const int g0 = wave * RPG + 4 * RPG * i;      // first tile row of the group (scalar)
+      if (GATED) {
+        // tile rows [w WN, w WN + WN/2) are gate rows, the next WN/2 the up rows of the same f
+        const int w = g0 / WN, within = g0 % WN;
+        const int f = min(it.nt * (BN / 2) + w * (WN / 2) + (within % (WN / 2)) + sub, p.N - 1);
+        cx.b_voff[i] = ((uint32_t)f * (uint32_t)p.K + c * 8) * 2;
+      } else {
+        const int n = min(it.nt * BN + g0 + sub, p.N - 1);
+        cx.b_voff[i] = ((uint32_t)n * (uint32_t)p.K + c * 8) * 2;
+      }
+    }
+    return cx;
+  };
 
   // Issues loads [first, last) of the LPS loads that fill one stage with k-tile kt
-  // (A row groups first, then B row groups).
-  auto issue_loads = [&](int kt, int stage, int first, int last) {
+  // of item cx (A row groups first, then B row groups).
+  auto issue_loads = [&](const Ctx& cx, int kt, int stage, int first, int last) {
     // wave-uniform LDS base of this wavefront's first row group; lane * 16 is implicit
     uint8_t* base = smem + stage * kStageBytes + wave * RPG * kRowBytes;
     const int koff = (kt_first + kt) * (BK * 2);
+    const __amdgpu_buffer_rsrc_t b0_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)cx.b0, 0, (int)p.b_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t b1_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)cx.b1, 0, (int)p.b_bytes, kBufferFlags);
 #pragma unroll
     for (int i = 0; i < A_CH; ++i)
       if (i >= first && i < last)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc, (lds_ptr_t)(base + i * 4 * RPG * kRowBytes),
-                                                 16, a_voff[i], koff, 0, 0);
+                                                 16, cx.a_voff[i], koff, 0, 0);
 #pragma unroll
     for (int i = 0; i < B_CH; ++i)
-      if (A_CH + i >= first && A_CH + i < last)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(b_up[i] ? b1_rsrc : b0_rsrc,
+      if (A_CH + i >= first && A_CH + i < last) {
+        const int g0 = wave * RPG + 4 * RPG * i;
+        const bool up = GATED && (g0 % WN) >= WN / 2;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(up ? b1_rsrc : b0_rsrc,
                                                  (lds_ptr_t)(base + (BM + i * 4 * RPG) * kRowBytes),
-                                                 16, b_voff[i], koff, 0, 0);
+                                                 16, cx.b_voff[i], koff, 0, 0);
+      }
   };
-
-  f32x16 acc[MI][NJ];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // operand rows of this lane inside the LDS tile
   const int a_off = (wm * WM + r32) * kRowBytes;          // + 32 i rows
@@ -277,41 +352,33 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   bf16x8 af[2][MI], bfr[2][NJ];
   auto read_frags = [&](int stage, int kk, int buf) {
     const uint8_t* base = smem + stage * kStageBytes;
-    const int slot = ((kk * 2 + q) ^ key_r) * 16;
+    const int slot_b = ((kk * 2 + q) ^ key_r) * 16;
     // in the order the MFMAs below consume them
-    af[buf][0] = *reinterpret_cast<const bf16x8*>(base + a_off + slot);
+    af[buf][0] = *reinterpret_cast<const bf16x8*>(base + a_off + slot_b);
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-      bfr[buf][j] = *reinterpret_cast<const bf16x8*>(base + b_off + j * 32 * kRowBytes + slot);
+      bfr[buf][j] = *reinterpret_cast<const bf16x8*>(base + b_off + j * 32 * kRowBytes + slot_b);
 #pragma unroll
     for (int i = 1; i < MI; ++i)
-      af[buf][i] = *reinterpret_cast<const bf16x8*>(base + a_off + i * 32 * kRowBytes + slot);
+      af[buf][i] = *reinterpret_cast<const bf16x8*>(base + a_off + i * 32 * kRowBytes + slot_b);
   };
 
-  // Ring protocol (STAGES >= 3).  The prologue fills stages 0..STAGES-2 with
-  // k-tiles 0..STAGES-2.  Iteration kt computes from stage kt % STAGES and, spread
-  // evenly over its MFMA steps, refills stage (kt - 1) % STAGES -- free since the
-  // barrier that ended iteration kt - 1 -- with k-tile kt + STAGES - 1.  In its last
-  // step the wavefront waits until k-tile kt + 1 has landed (vmcnt counts only the
+  f32x16 acc[MI][NJ];
+
+  // Ring protocol.  The k-tiles of this workgroup's items form one stream; stream
+  // position g is computed from stage g % STAGES.  The prologue fills stages
+  // 0..STAGES-2.  Iteration g, spread evenly over its MFMA steps, refills stage
+  // (g - 1) % STAGES -- free since the barrier that ended iteration g - 1 -- with
+  // stream position g + STAGES - 1 (which may belong to the next item).  In its last
+  // step the wavefront waits until position g + 1 has landed (vmcnt counts only the
   // younger loads), drains its own LDS reads, meets the others at the barrier and
-  // reads the first operands of k-tile kt + 1.  The last part of the refill is issued
-  // after the barrier so that it, too, sits among MFMAs.  Past the end the refill
-  // re-fetches the last k-tile into a stage nobody reads again, which keeps the
-  // vmcnt bookkeeping uniform.
-  static_assert(STAGES >= 3, "ring needs a free stage to refill during an iteration");
+  // reads the first operands of position g + 1.  The last part of the refill is
+  // issued after the barrier so that it, too, sits among MFMAs.
   constexpr int kPart = (LPS + KK - 1) / KK;     // most loads one step issues
-
-#pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) issue_loads(min(s, KT - 1), s, 0, LPS);
-  wait_vmcnt<(STAGES - 2) * LPS>();
-  __builtin_amdgcn_s_barrier();
-  read_frags(0, 0, 0);
-
-  int stage = 0;                       // kt % STAGES
-  int fill_stage = STAGES - 1;         // (kt + STAGES - 1) % STAGES
-  for (int kt = 0; kt < KT; ++kt) {
+  int stage = 0;                       // g % STAGES
+  int fill_stage = STAGES - 1;         // (g + STAGES - 1) % STAGES
+  auto k_iteration = [&](const Ctx& fill_cx, int fill_kt) {
     const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
-    const int fill_kt = min(kt + STAGES - 1, KT - 1);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       constexpr int kReads = MI + NJ;
@@ -324,7 +391,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
         __builtin_amdgcn_s_barrier();
         read_frags(next_stage, 0, (kk + 1) & 1);
       }
-      issue_loads(fill_kt, fill_stage, kk * LPS / KK, (kk + 1) * LPS / KK);
+      issue_loads(fill_cx, fill_kt, fill_stage, kk * LPS / KK, (kk + 1) * LPS / KK);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -351,54 +418,105 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     }
     stage = next_stage;
     fill_stage = fill_stage + 1 == STAGES ? 0 : fill_stage + 1;
-  }
+  };
 
-  // ---- epilogue ---------------------------------------------------------------
   // The weight rows are the MFMA's first operand, so accumulator register v of
   // lane (r32, q) is output row (activation row) r32 of subtile i and output
   // column 8 (v / 4) + 4 q + v % 4 of subtile j: four consecutive columns per
   // register quad, written as one 8-byte (bf16) or 16-byte (fp32 partial) store.
+  auto epilogue = [&](const Ctx& cx) {
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    const int row = wm * WM + i * 32 + r32;
-    if (row >= row_count) continue;
-    const size_t crow = (size_t)(row_start + row);
-    if (GATED) {
-      constexpr int NH = NJ / 2;
+    for (int i = 0; i < MI; ++i) {
+      const int row = wm * WM + i * 32 + r32;
+      if (row >= cx.row_count) continue;
+      const size_t crow = (size_t)(cx.row_start + row);
+      if (GATED) {
+        constexpr int NH = NJ / 2;
 #pragma unroll
-      for (int j = 0; j < NH; ++j)
+        for (int j = 0; j < NH; ++j)
 #pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-          const int f = nt * (BN / 2) + wn * (WN / 2) + j * 32 + vg * 8 + q * 4;
-          if (f < p.N) {
-            bf16x4 o;
+          for (int vg = 0; vg < 4; ++vg) {
+            const int f = cx.nt * (BN / 2) + wn * (WN / 2) + j * 32 + vg * 8 + q * 4;
+            if (f < p.N) {
+              bf16x4 o;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              o[e] = (bf16_t)(silu(acc[i][j][vg * 4 + e]) * acc[i][j + NH][vg * 4 + e]);
-            *reinterpret_cast<bf16x4*>(p.C + crow * p.N + f) = o;
+              for (int e = 0; e < 4; ++e)
+                o[e] = (bf16_t)(silu(acc[i][j][vg * 4 + e]) * acc[i][j + NH][vg * 4 + e]);
+              *reinterpret_cast<bf16x4*>(p.C + crow * p.N + f) = o;
+            }
           }
-        }
-    } else {
+      } else {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+          for (int vg = 0; vg < 4; ++vg) {
+            const int n = cx.nt * BN + wn * WN + j * 32 + vg * 8 + q * 4;
+            if (n < p.N) {
+              if (SPLITK) {
+                const f32x4 o = {acc[i][j][vg * 4], acc[i][j][vg * 4 + 1], acc[i][j][vg * 4 + 2],
+                                 acc[i][j][vg * 4 + 3]};
+                *reinterpret_cast<f32x4*>(p.Cpart + ((size_t)blockIdx.y * p.c_rows + crow) * p.N + n) = o;
+              } else {
+                bf16x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[i][j][vg * 4 + e];
+                *reinterpret_cast<bf16x4*>(p.C + crow * p.N + n) = o;
+              }
+            }
+          }
+      }
+    }
+  };
+
+  // ---- walk the items ---------------------------------------------------------------
+  // Item headers are fetched two items ahead and their pointers / source rows one
+  // item ahead, so nothing on the critical path waits for them.
+  int idx = slot;
+  Item it_cur = fetch_item(idx);
+  const Raw raw_cur = fetch_raw(it_cur);
+  wait_vmcnt<0>();                       // the first item's source rows
+  Ctx cur = make_ctx(it_cur, raw_cur);
+  Item it_next = fetch_item(idx + slots);
+
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s) issue_loads(cur, min(s, KT - 1), s, 0, LPS);
+  wait_vmcnt<(STAGES - 2) * LPS>();
+  __builtin_amdgcn_s_barrier();
+  read_frags(0, 0, 0);
+
+  while (true) {
+    const bool has_next = idx + slots < count;
+    const Item it_next2 = fetch_item(idx + 2 * slots);
+    const Item& it_fill = has_next ? it_next : it_cur;
+    const Raw raw_next = fetch_raw(it_fill);      // one more counted load, older than all that follow
+
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
 #pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-          const int n = nt * BN + wn * WN + j * 32 + vg * 8 + q * 4;
-          if (n < p.N) {
-            if (SPLITK) {
-              const f32x4 o = {acc[i][j][vg * 4], acc[i][j][vg * 4 + 1], acc[i][j][vg * 4 + 2],
-                               acc[i][j][vg * 4 + 3]};
-              *reinterpret_cast<f32x4*>(p.Cpart + ((size_t)blockIdx.y * p.c_rows + crow) * p.N + n) = o;
-            } else {
-              bf16x4 o;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[i][j][vg * 4 + e];
-              *reinterpret_cast<bf16x4*>(p.C + crow * p.N + n) = o;
-            }
-          }
-        }
-    }
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // refills still inside this item
+    for (int kt = 0; kt + (STAGES - 1) < KT; ++kt) k_iteration(cur, kt + STAGES - 1);
+    // The source rows of the next item were requested before those iterations; loads
+    // complete in order, so they have landed once enough younger loads have been
+    // waited for, which the iterations above guarantee only if there were enough.
+    if (GATED && KT < 2 * (STAGES - 1)) wait_vmcnt<0>();
+    // refills that already belong to the next item (for the last item: a harmless
+    // re-fetch of this item's first k-tiles, which keeps the vmcnt bookkeeping uniform)
+    const Ctx nxt = make_ctx(it_fill, raw_next);
+    for (int kt = max(KT - (STAGES - 1), 0); kt < KT; ++kt)
+      k_iteration(nxt, min(kt + (STAGES - 1) - KT, KT - 1));
+
+    epilogue(cur);
+    if (!has_next) break;
+    cur = nxt;
+    it_cur = it_next;
+    it_next = it_next2;
+    idx += slots;
   }
+  wait_vmcnt<0>();   // the last refills must land before this LDS allocation is released
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
@@ -407,21 +525,30 @@ static inline int max_row_tiles(const prism_layer_desc& d, int T, int BM) {
   return T * d.top_k / BM + d.n_experts + d.n_shared * ceil_div(T, BM);
 }
 
+// Items one XCD list must be able to hold: every row tile times its share of the column tiles.
+static inline int sched_capacity(const prism_layer_desc& d, int T, int BM, int n_ntiles) {
+  return max_row_tiles(d, T, BM) * ceil_div(n_ntiles, kXcds);
+}
+
 // Launches the schedule builder for one GEMM: row tile BM, n_ntiles column tiles.
 static inline prism_status launch_build_schedule(const prism_layer_desc& d,
                                                  const int32_t* local_offsets, int T, int BM,
-                                                 int n_ntiles, int32_t* tiles, hipStream_t st) {
+                                                 int n_ntiles, int32_t* sched, hipStream_t st) {
   hipLaunchKernelGGL(build_schedule_kernel, dim3(1), dim3(512), 0, st, local_offsets, d.n_experts,
-                     d.n_shared, T, T * d.top_k, BM, ceil_div(n_ntiles, kXcds),
-                     max_row_tiles(d, T, BM), tiles);
+                     d.n_shared, T, T * d.top_k, BM, n_ntiles, sched_capacity(d, T, BM, n_ntiles),
+                     sched);
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;
 }
 
+// capacity: items per XCD list (sched_capacity).  The grid holds as many workgroups
+// as fit on the machine at once (each then walks several items), or one per item.
 template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false>
-prism_status launch_gemm(const GemmArgs& args, int max_mtiles, hipStream_t st, int n_splits = 1) {
-  constexpr int smem = STAGES * (BM + BN) * BK * 2;
+prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int n_splits = 1) {
+  constexpr int smem = STAGES * (BM + BN) * BK * 2 + (GATED ? 4096 : 0);   // ring + source-row slots
   static_assert(smem <= 160 * 1024, "LDS per workgroup");
+  constexpr int kCusPerXcd = 32;
+  constexpr int kResident = (160 * 1024) / smem;     // workgroups per CU that fit in LDS
   auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -429,11 +556,12 @@ prism_status launch_gemm(const GemmArgs& args, int max_mtiles, hipStream_t st, i
       return PRISM_ERR_LAUNCH;
     attr_set = true;
   }
-  const long long blocks = (long long)max_mtiles * ceil_div(args.n_ntiles, kXcds) * kXcds;
-  if (blocks <= 0) return PRISM_OK;
-  if (blocks > 0x7fffffffLL) return PRISM_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks, SPLITK ? n_splits : 1), dim3(kGemmThreads), smem,
-                     st, args);
+  if (capacity <= 0) return PRISM_OK;
+  const int splits = SPLITK ? n_splits : 1;
+  int slots = kCusPerXcd * kResident / splits;       // persistent workgroups per XCD
+  if (slots < 1) slots = 1;
+  if (slots > capacity) slots = capacity;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(slots * kXcds), splits), dim3(kGemmThreads), smem, st, args);
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;
 }

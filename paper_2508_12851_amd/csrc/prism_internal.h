@@ -46,13 +46,14 @@ struct Workspace {
 
 static inline int elem_size(int dtype) { return dtype == PRISM_F32 ? 4 : 2; }
 
-// ints in one GEMM schedule: header, 4 per row tile, 2 per work item (row tile x column octet)
+// ints in one GEMM schedule: a 16-int header, then 8 per-XCD lists of 8-int work items; a list
+// holds at most (row tiles) x ceil(column tiles / 8) items (bounds for the smallest tiles used)
 static inline size_t tile_table_ints(const prism_layer_desc& d, int T) {
   const size_t A = (size_t)T * d.top_k;
   const size_t mt = A / kMinTileM + d.n_experts + (size_t)d.n_shared * ceil_div(T > 0 ? T : 1, kMinTileM) + 1;
   const int wide = d.ffn > d.hidden ? d.ffn : d.hidden;
   const size_t nj8 = ceil_div(ceil_div(wide > 0 ? wide : 1, 64), 8);
-  return align_up(4 + 4 * mt + 2 * mt * nj8, 64);
+  return align_up(16 + 8 * 8 * mt * nj8, 64);
 }
 
 static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
