@@ -234,8 +234,9 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
 
   // bf16: schedules for the two GEMMs, then the GEMMs.  Buffer addressing uses
   // 32-bit byte offsets, so every operand matrix must stay below 4 GiB.
-  if ((size_t)T * d.hidden * 2 >= (1ull << 32) || (size_t)rows * d.ffn * 2 >= (1ull << 32) ||
-      (size_t)d.ffn * d.hidden * 2 >= (1ull << 32))
+  constexpr size_t kMaxOperandBytes = 0xFFFF0000ull;
+  if ((size_t)T * d.hidden * 2 >= kMaxOperandBytes || (size_t)rows * d.ffn * 2 >= kMaxOperandBytes ||
+      (size_t)d.ffn * d.hidden * 2 >= kMaxOperandBytes)
     return PRISM_ERR_UNSUPPORTED;
   if (T <= kDecodeMaxTokens) {
     // Decode batch: every expert has at most 64 rows, the layer is bound by streaming

@@ -165,8 +165,13 @@ typedef const __attribute__((address_space(4))) int4* const_int4_ptr;
 typedef const __attribute__((address_space(4))) int32_t* const_int_ptr;
 typedef const void* const __attribute__((address_space(4)))* const_ptr_table;
 constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
+constexpr uint32_t kOutOfRange = 0xFFFFFF00u;   // above every operand size (those stay below 0xFFFF0000)
 
-__device__ __forceinline__ float silu(float z) { return z / (1.0f + __expf(-z)); }
+// silu(z) = z / (1 + e^-z) with the hardware exp2 and reciprocal (each within 1 ulp;
+// the result is rounded to bf16 right after).
+__device__ __forceinline__ float silu(float z) {
+  return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * z));
+}
 
 // LDS slot swizzle.  The LDS serves a 16-byte-per-lane read 16 lanes (256 bytes,
 // 64 banks) per cycle, so 16 consecutive rows read at the same logical chunk
@@ -300,7 +305,10 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
       } else {
         src = (uint32_t)(it.row_start + rr);
       }
-      cx.a_voff[i] = (src * (uint32_t)p.K + c * 8) * 2;
+      // Rows past the end of a partly filled tile get an offset beyond the buffer: the
+      // hardware then returns zeros, and all-zero operands cost the matrix cores far
+      // less power than real data (the chip is power-limited in this kernel).
+      cx.a_voff[i] = lrow + 4 * RPG * i < it.row_count ? (src * (uint32_t)p.K + c * 8) * 2 : kOutOfRange;
     }
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) {
@@ -345,7 +353,9 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   };
 
   // operand rows of this lane inside the LDS tile
-  const int a_off = (wm * WM + r32) * kRowBytes;          // + 32 i rows
+  // Row subtile i of this wavefront is tile rows 32 (i WGM + wm) .. (the subtiles of
+  // the WGM wavefront rows interleave).
+  const int a_off = (wm * 32 + r32) * kRowBytes;          // + 32 WGM i rows
   const int b_off = (BM + wn * WN + r32) * kRowBytes;     // + 32 j rows
   const int key_r = swizzle_key<BK>(r32);
 
@@ -360,7 +370,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
       bfr[buf][j] = *reinterpret_cast<const bf16x8*>(base + b_off + j * 32 * kRowBytes + slot_b);
 #pragma unroll
     for (int i = 1; i < MI; ++i)
-      af[buf][i] = *reinterpret_cast<const bf16x8*>(base + a_off + i * 32 * kRowBytes + slot_b);
+      af[buf][i] = *reinterpret_cast<const bf16x8*>(base + a_off + i * WGM * 32 * kRowBytes + slot_b);
   };
 
   f32x16 acc[MI][NJ];
@@ -427,7 +437,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   auto epilogue = [&](const Ctx& cx) {
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
-      const int row = wm * WM + i * 32 + r32;
+      const int row = (i * WGM + wm) * 32 + r32;
       if (row >= cx.row_count) continue;
       const size_t crow = (size_t)(cx.row_start + row);
       if (GATED) {
