@@ -98,7 +98,7 @@ prism_status prism_dispatch(const prism_layer_desc* desc, const int32_t* topk_id
   PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
   return launch_dispatch(*desc, topk_idx, local_mask, T, local_src, local_offsets, remote_src,
                          remote_offsets, n_local_remote, remote_bytes, nullptr, ws.block_hist,
-                         (hipStream_t)stream);
+                         nullptr, nullptr, (hipStream_t)stream);
 }
 
 prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
@@ -112,7 +112,7 @@ prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
   Workspace ws;
   PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
   return launch_expert_ffn(*desc, x, *weights, local_src, local_offsets, T, y, ws.h, ws.tiles,
-                           ws.part, (hipStream_t)stream, nullptr);
+                           ws.part, (hipStream_t)stream, nullptr, nullptr);
 }
 
 prism_status prism_combine(const prism_layer_desc* desc, const void* y, const int32_t* local_src,
@@ -152,19 +152,30 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
   PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
   const hipStream_t st = (hipStream_t)stream;
   void* const* ev = stage_events;
-  trace(ev, PRISM_STAGE_ROUTE, 0, st);
-  PRISM_TRY(launch_route(*desc, x, w_router, router_bias, T, nullptr, topk_idx, topk_gate, counts,
-                         counts_accum, st));
-  trace(ev, PRISM_STAGE_ROUTE, 1, st);
-  trace(ev, PRISM_STAGE_DISPATCH, 0, st);
-  PRISM_TRY(launch_dispatch(*desc, topk_idx, local_mask, T, ws.local_src, ws.local_offsets,
-                            remote_src, remote_offsets, n_local_remote, remote_bytes, ws.inv,
-                            ws.block_hist, st));
-  trace(ev, PRISM_STAGE_DISPATCH, 1, st);
-  PRISM_TRY(launch_expert_ffn(*desc, x, *weights, ws.local_src, ws.local_offsets, T, ws.y, ws.h,
-                              ws.tiles, ws.part, st, ev));
+  int n_splits = 0;
+  if (decode_front_end_applies(*desc, T)) {
+    PRISM_TRY(launch_decode_front_end(*desc, x, w_router, router_bias, local_mask, T, topk_idx,
+                                      topk_gate, counts, counts_accum, ws.local_src,
+                                      ws.local_offsets, remote_src, remote_offsets, n_local_remote,
+                                      remote_bytes, ws.inv, ws.route_part, ws.tiles, st, ev));
+    PRISM_TRY(launch_expert_ffn(*desc, x, *weights, ws.local_src, ws.local_offsets, T, ws.y, ws.h,
+                                ws.tiles, ws.part, st, ev, &n_splits, true));
+  } else {
+    trace(ev, PRISM_STAGE_ROUTE, 0, st);
+    // the activation counts come out of the dispatch histogram, not out of the router
+    PRISM_TRY(launch_route(*desc, x, w_router, router_bias, T, nullptr, topk_idx, topk_gate, nullptr,
+                           nullptr, st));
+    trace(ev, PRISM_STAGE_ROUTE, 1, st);
+    trace(ev, PRISM_STAGE_DISPATCH, 0, st);
+    PRISM_TRY(launch_dispatch(*desc, topk_idx, local_mask, T, ws.local_src, ws.local_offsets,
+                              remote_src, remote_offsets, n_local_remote, remote_bytes, ws.inv,
+                              ws.block_hist, counts, counts_accum, st));
+    trace(ev, PRISM_STAGE_DISPATCH, 1, st);
+    PRISM_TRY(launch_expert_ffn(*desc, x, *weights, ws.local_src, ws.local_offsets, T, ws.y, ws.h,
+                                ws.tiles, ws.part, st, ev, &n_splits));
+  }
   trace(ev, PRISM_STAGE_COMBINE, 0, st);
-  PRISM_TRY(launch_combine(*desc, ws.y, ws.inv, topk_gate, T, out, st));
+  PRISM_TRY(launch_combine(*desc, ws.y, ws.inv, topk_gate, T, out, st, ws.part, n_splits));
   trace(ev, PRISM_STAGE_COMBINE, 1, st);
   return PRISM_OK;
 }

@@ -6,6 +6,10 @@
 //
 // fp32 accumulation, one rounding to the layer dtype.  HBM-bound: every thread
 // moves 16 bytes per y row it touches.
+//
+// Decode batches leave the down projection as fp32 contraction slices; the
+// fused layer then reads y from them: every element is the slice sum in slice
+// order, rounded to bf16 exactly as the finished y row would have stored it.
 #include "prism_internal.h"
 
 namespace prism {
@@ -78,6 +82,83 @@ __global__ __launch_bounds__(256) void combine_kernel(const TIO* __restrict__ y,
   Vec<TIO>::store(out + (size_t)t * H + col, acc);
 }
 
+// Same aggregation with y taken from the contraction slices (bf16 layers).  Four
+// columns per thread: a decode batch has few tokens, and the narrower vectors put
+// twice as many workgroups on the machine.  The kernel is a chain of dependent
+// memory round trips (slot table, then rows), so the slot table of a token is read
+// in one go and the slice loads of two rows are issued together.
+struct SliceRow {
+  f32x4 v[kDecodeSplits];
+};
+__device__ __forceinline__ void load_slices(const float* __restrict__ part, int n_splits,
+                                            size_t rows, int H, size_t row, int col, bool on,
+                                            SliceRow& r) {
+#pragma unroll
+  for (int s = 0; s < kDecodeSplits; ++s)
+    if (on && s < n_splits)
+      r.v[s] = *reinterpret_cast<const f32x4*>(part + ((size_t)s * rows + row) * H + col);
+}
+// Slice sum in slice order, rounded to bf16: what the finished y row would hold.
+__device__ __forceinline__ f32x4 sum_slices(const SliceRow& r, int n_splits) {
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < kDecodeSplits; ++s)
+    if (s < n_splits) sum += r.v[s];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) sum[i] = (float)(bf16_t)sum[i];
+  return sum;
+}
+
+__global__ __launch_bounds__(256) void combine_slices_kernel(const float* __restrict__ part,
+                                                             int n_splits,
+                                                             const int32_t* __restrict__ inv,
+                                                             const float* __restrict__ gate, int T,
+                                                             int H, int k, int S,
+                                                             uint16_t* __restrict__ out) {
+  const int vec_per_row = H / 4;
+  const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long long)T * vec_per_row) return;
+  const int t = (int)(gid / vec_per_row);
+  const int col = (int)(gid - (long long)t * vec_per_row) * 4;
+  const size_t A = (size_t)T * k;
+  const size_t rows = A + (size_t)S * T;
+  int row_of[PRISM_MAX_TOPK];
+  float gate_of[PRISM_MAX_TOPK];
+#pragma unroll
+  for (int j = 0; j < PRISM_MAX_TOPK; ++j) {
+    row_of[j] = j < k ? inv[t * k + j] : -1;
+    gate_of[j] = j < k ? gate[t * k + j] : 0.f;
+  }
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < PRISM_MAX_TOPK; j += 2) {
+    if (j >= k) break;
+    SliceRow r0, r1;
+    const bool on0 = row_of[j] >= 0, on1 = row_of[j + 1] >= 0;
+    load_slices(part, n_splits, rows, H, (size_t)(on0 ? row_of[j] : 0), col, on0, r0);
+    load_slices(part, n_splits, rows, H, (size_t)(on1 ? row_of[j + 1] : 0), col, on1, r1);
+    if (on0) {
+      const f32x4 v = sum_slices(r0, n_splits);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = fmaf(gate_of[j], v[i], acc[i]);
+    }
+    if (on1) {
+      const f32x4 v = sum_slices(r1, n_splits);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = fmaf(gate_of[j + 1], v[i], acc[i]);
+    }
+  }
+  for (int s = 0; s < S; ++s) {
+    SliceRow r;
+    load_slices(part, n_splits, rows, H, A + (size_t)s * T + t, col, true, r);
+    acc += sum_slices(r, n_splits);
+  }
+  bf16x4 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = (bf16_t)acc[i];
+  *reinterpret_cast<bf16x4*>(out + (size_t)t * H + col) = o;
+}
+
 }  // namespace
 
 prism_status launch_build_inverse(const prism_layer_desc& d, const int32_t* local_src,
@@ -93,8 +174,19 @@ prism_status launch_build_inverse(const prism_layer_desc& d, const int32_t* loca
 }
 
 prism_status launch_combine(const prism_layer_desc& d, const void* y, const int32_t* inv,
-                            const float* topk_gate, int T, void* out, hipStream_t st) {
+                            const float* topk_gate, int T, void* out, hipStream_t st,
+                            const float* part, int n_splits) {
   if (T == 0) return PRISM_OK;
+  if (n_splits > 0 && (d.dtype != PRISM_BF16 || part == nullptr || n_splits > kDecodeSplits))
+    return PRISM_ERR_INVALID_ARG;
+  if (n_splits > 0) {
+    const long long threads = (long long)T * (d.hidden / 4);
+    hipLaunchKernelGGL(combine_slices_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
+                       st, part, n_splits, inv, topk_gate, T, d.hidden, d.top_k, d.n_shared,
+                       (uint16_t*)out);
+    PRISM_CHECK_LAUNCH();
+    return PRISM_OK;
+  }
   const int n = d.dtype == PRISM_F32 ? 4 : 8;
   const long long threads = (long long)T * (d.hidden / n);
   const unsigned blocks = (unsigned)((threads + 255) / 256);

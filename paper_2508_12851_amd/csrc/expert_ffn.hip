@@ -149,8 +149,9 @@ template <typename C1, typename C2, bool SPLIT_DOWN>
 prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_expert_weights& w,
                           const int32_t* local_src, const int32_t* local_offsets, int T, void* y,
                           void* h, int32_t* tiles, float* part, hipStream_t st,
-                          void* const* stage_events) {
+                          void* const* stage_events, int* deferred_splits, bool schedules_built) {
   using gg::GemmArgs;
+  constexpr bool kRotate = SPLIT_DOWN;   // the decode path: no weight tile is shared between items
   const int A = T * d.top_k;
   const int rows = A + d.n_shared * T;
   // the k-tile ring of a workgroup must not be longer than its contraction slice
@@ -159,8 +160,8 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   int32_t* sched2 = tiles + tile_table_ints(d, T);
   const int nt1 = ceil_div(d.ffn, C1::BN / 2);     // GEMM1 tile: BN/2 gate rows + BN/2 up rows
   const int nt2 = ceil_div(d.hidden, C2::BN);
-  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, C1::BM, nt1, sched1, st));
-  PRISM_TRY(gg::launch_build_schedule(d, local_offsets, T, C2::BM, nt2, sched2, st));
+  if (!schedules_built)
+    PRISM_TRY(gg::launch_build_schedules(d, local_offsets, T, C1::BM, nt1, sched1, C2::BM, nt2, sched2, st));
 
   GemmArgs g1{};
   g1.A = (const uint16_t*)x;
@@ -172,7 +173,7 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   g1.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g1.K = d.hidden; g1.N = d.ffn; g1.top_k = d.top_k; g1.E = d.n_experts;
   trace(stage_events, PRISM_STAGE_FFN_UP, 0, st);
-  PRISM_TRY((gg::launch_gemm<C1::BM, C1::BN, 2, 2, C1::BK, C1::STAGES, true>(
+  PRISM_TRY((gg::launch_gemm<C1::BM, C1::BN, 2, 2, C1::BK, C1::STAGES, true, false, kRotate>(
       g1, gg::sched_capacity(d, T, C1::BM, nt1), st)));
   trace(stage_events, PRISM_STAGE_FFN_UP, 1, st);
 
@@ -192,9 +193,11 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
     if (n_splits > kDecodeSplits) n_splits = kDecodeSplits;
   }
   trace(stage_events, PRISM_STAGE_FFN_DOWN, 0, st);
-  PRISM_TRY((gg::launch_gemm<C2::BM, C2::BN, 2, 2, C2::BK, C2::STAGES, false, SPLIT_DOWN>(
+  PRISM_TRY((gg::launch_gemm<C2::BM, C2::BN, 2, 2, C2::BK, C2::STAGES, false, SPLIT_DOWN, kRotate>(
       g2, gg::sched_capacity(d, T, C2::BM, nt2), st, n_splits)));
-  if (SPLIT_DOWN) {
+  if (SPLIT_DOWN && deferred_splits != nullptr) {
+    *deferred_splits = n_splits;   // the caller's combine sums the slices itself
+  } else if (SPLIT_DOWN) {
     const long long threads = (long long)rows * (d.hidden / 4);
     hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
                        part, local_offsets, d.n_experts, A, rows, d.hidden, n_splits, (uint16_t*)y);
@@ -210,7 +213,9 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
                                int32_t* tiles, float* part, hipStream_t st,
-                               void* const* stage_events) {
+                               void* const* stage_events, int* deferred_splits,
+                               bool schedules_built) {
+  if (deferred_splits != nullptr) *deferred_splits = 0;
   if (T == 0) return PRISM_OK;
   const int A = T * d.top_k;
   const int rows = A + d.n_shared * T;
@@ -240,21 +245,31 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
     return PRISM_ERR_UNSUPPORTED;
   if (T <= kDecodeMaxTokens) {
     // Decode batch: every expert has at most 64 rows, the layer is bound by streaming
-    // the weights once.  Small tiles put ~1000 workgroups on the machine; the down
-    // projection also splits its contraction and a last kernel sums the slices.
+    // the weights once.  Small tiles make ~1000 work items; the down projection also
+    // splits its contraction (the slices are summed by a last kernel or by the combine).
+    // No weight tile is shared between workgroups here, so every item starts its
+    // contraction at a different k-tile: at any moment the workgroups then read
+    // different column ranges of the weight rows, whose power-of-two pitch would
+    // otherwise send them all to the same few memory channels.
+    // (decode_schedule_shapes() below states the tile shapes of both variants)
     if (d.hidden >= 192 && d.ffn >= 192)
       return run_bf16_ffn<TileCfg<64, 128, 64, 4>, TileCfg<64, 128, 64, 4>, true>(
-          d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
+          d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
     return run_bf16_ffn<TileCfg<64, 128, 32, 3>, TileCfg<64, 128, 32, 3>, true>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
   }
   // Prefill batch: 256 x 256 tiles (GEMM1: 128 gate + 128 up weight rows).  Very short
   // contractions (H or F of 64) get the shallowest ring.
   if (d.hidden >= 128 && d.ffn >= 128)
     return run_bf16_ffn<TileCfg<256, 256, 32, 4>, TileCfg<256, 256, 32, 4>, false>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
   return run_bf16_ffn<TileCfg<256, 256, 32, 3>, TileCfg<256, 256, 32, 3>, false>(
-      d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events);
+      d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
+}
+
+void decode_schedule_shapes(const prism_layer_desc& d, int* bm1, int* nt1, int* bm2, int* nt2) {
+  *bm1 = 64; *nt1 = ceil_div(d.ffn, 128 / 2);
+  *bm2 = 64; *nt2 = ceil_div(d.hidden, 128);
 }
 
 }  // namespace prism

@@ -36,103 +36,17 @@
 #define PRISM_GROUPED_GEMM_H_
 
 #include "prism_internal.h"
+#include "schedule.h"
 
 namespace prism {
 namespace gg {
 
-constexpr int kMaxGroups = PRISM_MAX_EXPERTS + PRISM_MAX_SHARED;
-constexpr int kXcds = 8;
-constexpr int kSchedHeader = 16;     // ints
-constexpr int kItemInts = 8;         // ints per work item
-
-// Schedule memory (int32):
-//   [0] n_mtiles  [1] capacity of one XCD list (items)  [4 + x] items in the list of XCD x
-//   then, from int kSchedHeader on, 8 lists of `capacity` items of 8 ints:
-//     [0] group id g (g < E: routed expert g; else shared expert g - E)
-//     [1] first row of the row tile in h / y row space
-//     [2] rows in the tile (1..BM)
-//     [3] first token of the tile for shared experts, -1 for routed ones
-//     [4] column tile
+// Workgroup b builds the schedule p[b] (one launch serves both GEMMs of the FFN).
 __global__ __launch_bounds__(512) void build_schedule_kernel(
-    const int32_t* __restrict__ local_offsets, int E, int S, int T, int A_total, int BM,
-    int n_ntiles, int capacity, int32_t* __restrict__ sched) {
-  __shared__ int s_start[kMaxGroups + 1];            // first row tile of group g
-  __shared__ int s_rows[kMaxGroups], s_row0[kMaxGroups];
-  __shared__ int s_rank[kMaxGroups];                 // index of g among the non-empty groups
-  __shared__ int s_base[kXcds][kMaxGroups + 1];      // items of XCD x before group g
-  const int G = E + S;
-  for (int g = threadIdx.x; g < G; g += blockDim.x) {
-    int rows, row0;
-    if (g < E) {
-      row0 = local_offsets[g];
-      rows = local_offsets[g + 1] - row0;
-    } else {
-      row0 = A_total + (g - E) * T;
-      rows = T;
-    }
-    s_rows[g] = rows;
-    s_row0[g] = row0;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0, rank = 0;
-    for (int g = 0; g < G; ++g) {
-      s_start[g] = run;
-      s_rank[g] = rank;
-      const int m = (s_rows[g] + BM - 1) / BM;
-      run += m;
-      rank += m > 0;
-    }
-    s_start[G] = run;
-    sched[0] = run;
-    sched[1] = capacity;
-  }
-  __syncthreads();
-  // Pair (g, nt) has index q = rank(g) * n_ntiles + nt and belongs to XCD q % 8.
-  // XCD x owns the column tiles r, r + 8, ... of group g with r = (x - rank(g) n_ntiles) mod 8.
-  auto first_nt = [&](int g, int x) {
-    const int r = (x - s_rank[g] * n_ntiles) % kXcds;
-    return r < 0 ? r + kXcds : r;
-  };
-  if (threadIdx.x < kXcds) {
-    const int x = threadIdx.x;
-    int run = 0;
-    for (int g = 0; g < G; ++g) {
-      s_base[x][g] = run;
-      const int m = s_start[g + 1] - s_start[g];
-      const int r = first_nt(g, x);
-      const int c = r < n_ntiles ? (n_ntiles - 1 - r) / kXcds + 1 : 0;
-      run += m * c;
-    }
-    s_base[x][G] = run;
-    sched[4 + x] = run;
-  }
-  __syncthreads();
-  const int n_mtiles = s_start[G];
-  auto group_of_tile = [&](int i) {   // largest g with s_start[g] <= i (skips empty groups)
-    int lo = 0, hi = G;               // invariant: s_start[lo] <= i < s_start[hi]
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (s_start[mid] <= i) lo = mid; else hi = mid;
-    }
-    return lo;
-  };
-  const long long n_items = (long long)n_mtiles * n_ntiles;
-  for (long long w = threadIdx.x; w < n_items; w += blockDim.x) {
-    const int i = (int)(w % n_mtiles), nt = (int)(w / n_mtiles);
-    const int g = group_of_tile(i);
-    const int mi = i - s_start[g];
-    const int m = s_start[g + 1] - s_start[g];
-    const int x = (s_rank[g] * n_ntiles + nt) % kXcds;
-    const int pos = s_base[x][g] + ((nt - first_nt(g, x)) / kXcds) * m + mi;   // row tiles fastest
-    int32_t* out = sched + kSchedHeader + ((size_t)x * capacity + pos) * kItemInts;
-    out[0] = g;
-    out[1] = s_row0[g] + mi * BM;
-    out[2] = min(BM, s_rows[g] - mi * BM);
-    out[3] = g < E ? -1 : mi * BM;
-    out[4] = nt;
-    out[5] = 0; out[6] = 0; out[7] = 0;
-  }
+    const int32_t* __restrict__ local_offsets, int E, int S, int T, int A_total,
+    const SchedParams p0, const SchedParams p1) {
+  const SchedParams p[1] = {blockIdx.x == 0 ? p0 : p1};
+  build_schedules_block<1>(local_offsets, E, S, T, A_total, p);
 }
 
 struct GemmArgs {
@@ -190,7 +104,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // BK contraction elements per LDS stage (32 or 64), STAGES stages in flight.
 // SPLITK: blockIdx.y selects a slice of the contraction; the tile is written as
 // fp32 partial sums to p.Cpart[slice][row][col] (plain GEMM only).
-template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false>
+// ROTATE: every item walks its k-tiles cyclically from an item-dependent start, so
+// concurrent workgroups read different column ranges of their weight rows (for
+// schedules in which workgroups share no weight tiles, i.e. one row tile per group).
+template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false,
+          bool ROTATE = false>
 __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmArgs p) {
 #if defined(__HIP_DEVICE_COMPILE__)   // buffer resources exist in device code only
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
@@ -216,10 +134,16 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   // ---- this workgroup's items: slot, slot + slots, ... of its XCD's list -----------
   const int xcd = blockIdx.x % kXcds;
   const int slot = blockIdx.x / kXcds;
-  const int slots = gridDim.x / kXcds;
   const const_int_ptr sched_c = (const_int_ptr)p.sched;
   const int count = sched_c[4 + xcd];
   if (slot >= count) return;
+  // The list takes ceil(count / launched slots) rounds; the fewest workgroups that still
+  // finish in that many rounds share it evenly (a workgroup that would sit out the last
+  // round only takes memory bandwidth from the others in the rounds before).
+  const int launched = gridDim.x / kXcds;
+  const int rounds = (count + launched - 1) / launched;
+  const int slots = (count + rounds - 1) / rounds;
+  if (slot >= slots) return;
   const const_int4_ptr items =
       (const_int4_ptr)(p.sched + kSchedHeader) + (size_t)xcd * sched_c[1] * (kItemInts / 4);
 
@@ -255,6 +179,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   // What the loads and the epilogue of an item need.
   struct Ctx {
     int row_start, row_count, nt;
+    int rot;                 // ROTATE: k-tile this item starts its contraction with
     const void* b0;
     const void* b1;
     uint32_t a_voff[A_CH];
@@ -294,6 +219,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   auto make_ctx = [&](const Item& it, const Raw& raw) {
     Ctx cx;
     cx.row_start = it.row_start; cx.row_count = it.row_count; cx.nt = it.nt;
+    cx.rot = ROTATE ? (int)((unsigned)(it.nt * 13 + it.g * 29) % (unsigned)KT) : 0;
     cx.b0 = raw.b0; cx.b1 = raw.b1;
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
@@ -331,7 +257,12 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   auto issue_loads = [&](const Ctx& cx, int kt, int stage, int first, int last) {
     // wave-uniform LDS base of this wavefront's first row group; lane * 16 is implicit
     uint8_t* base = smem + stage * kStageBytes + wave * RPG * kRowBytes;
-    const int koff = (kt_first + kt) * (BK * 2);
+    int kt_mem = kt;
+    if (ROTATE) {
+      kt_mem += cx.rot;
+      if (kt_mem >= KT) kt_mem -= KT;
+    }
+    const int koff = (kt_first + kt_mem) * (BK * 2);
     const __amdgpu_buffer_rsrc_t b0_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)cx.b0, 0, (int)p.b_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t b1_rsrc =
@@ -530,36 +461,31 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
-// Upper bound on the number of row tiles for T tokens (host side).
-static inline int max_row_tiles(const prism_layer_desc& d, int T, int BM) {
-  return T * d.top_k / BM + d.n_experts + d.n_shared * ceil_div(T, BM);
-}
-
-// Items one XCD list must be able to hold: every row tile times its share of the column tiles.
-static inline int sched_capacity(const prism_layer_desc& d, int T, int BM, int n_ntiles) {
-  return max_row_tiles(d, T, BM) * ceil_div(n_ntiles, kXcds);
-}
-
-// Launches the schedule builder for one GEMM: row tile BM, n_ntiles column tiles.
-static inline prism_status launch_build_schedule(const prism_layer_desc& d,
-                                                 const int32_t* local_offsets, int T, int BM,
-                                                 int n_ntiles, int32_t* sched, hipStream_t st) {
-  hipLaunchKernelGGL(build_schedule_kernel, dim3(1), dim3(512), 0, st, local_offsets, d.n_experts,
-                     d.n_shared, T, T * d.top_k, BM, n_ntiles, sched_capacity(d, T, BM, n_ntiles),
-                     sched);
+// Launches the schedule builder for the two GEMMs of the FFN: row tiles bm1 / bm2,
+// nt1 / nt2 column tiles.
+static inline prism_status launch_build_schedules(const prism_layer_desc& d,
+                                                  const int32_t* local_offsets, int T, int bm1,
+                                                  int nt1, int32_t* sched1, int bm2, int nt2,
+                                                  int32_t* sched2, hipStream_t st) {
+  const SchedParams p0{bm1, nt1, sched_capacity(d, T, bm1, nt1), sched1};
+  const SchedParams p1{bm2, nt2, sched_capacity(d, T, bm2, nt2), sched2};
+  hipLaunchKernelGGL(build_schedule_kernel, dim3(2), dim3(512), 0, st, local_offsets, d.n_experts,
+                     d.n_shared, T, T * d.top_k, p0, p1);
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;
 }
 
 // capacity: items per XCD list (sched_capacity).  The grid holds as many workgroups
 // as fit on the machine at once (each then walks several items), or one per item.
-template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false>
-prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int n_splits = 1) {
+template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false,
+          bool ROTATE = false>
+prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int n_splits = 1,
+                         int max_slots = 0) {
   constexpr int smem = STAGES * (BM + BN) * BK * 2 + (GATED ? 4096 : 0);   // ring + source-row slots
   static_assert(smem <= 160 * 1024, "LDS per workgroup");
   constexpr int kCusPerXcd = 32;
   constexpr int kResident = (160 * 1024) / smem;     // workgroups per CU that fit in LDS
-  auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK>;
+  auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK, ROTATE>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -570,6 +496,7 @@ prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int
   const int splits = SPLITK ? n_splits : 1;
   int slots = kCusPerXcd * kResident / splits;       // persistent workgroups per XCD
   if (slots < 1) slots = 1;
+  if (max_slots > 0) slots = max_slots;
   if (slots > capacity) slots = capacity;
   hipLaunchKernelGGL(kernel, dim3((unsigned)(slots * kXcds), splits), dim3(kGemmThreads), smem, st, args);
   PRISM_CHECK_LAUNCH();

@@ -31,6 +31,8 @@ constexpr int kDispatchChunk = 2048;   // assignments per dispatch block
 constexpr int kDecodeMaxTokens = 64;    // batches up to this size take the weight-streaming path
 constexpr int kDecodeSplits = 8;        // contraction slices of its down projection
 constexpr int kMinTileM = 64;           // smallest row tile of the grouped GEMM (bounds table sizes)
+constexpr int kRouteTokTile = 16;       // tokens per router tile
+constexpr int kRouteMaxHSplit = 16;     // hidden-dimension slices of the decode router
 
 struct Workspace {
   int32_t* local_src;      // [A]
@@ -40,11 +42,20 @@ struct Workspace {
   int32_t* tiles;          // 2 x [tile_table_ints]: schedules of the two grouped GEMMs
   void* h;                 // [(A + S*T) * F] layer dtype: silu(gate)*up
   void* y;                 // [(A + S*T) * H] layer dtype: expert outputs
-  float* part;             // decode batches only: [kDecodeSplits][A + S*T][H] fp32 partial sums
+  float* part;             // decode batches: [kDecodeSplits][A + S*T][H] fp32 partial sums
+  double* route_part;      // decode batches: [token tiles][kRouteMaxHSplit][route_col_tiles][64][4] fp64
   size_t total;
 };
 
 static inline int elem_size(int dtype) { return dtype == PRISM_F32 ? 4 : 2; }
+
+// 16-expert column tiles of the router kernels: ceil(E / 16) rounded up to a power of two
+// (the kernels are instantiated for 1, 2, 4, 8 and 16 tiles).
+static inline int route_col_tiles(int n_experts) {
+  int nt = 1;
+  while (nt * 16 < n_experts) nt *= 2;
+  return nt;
+}
 
 // ints in one GEMM schedule: a 16-int header, then 8 per-XCD lists of 8-int work items; a list
 // holds at most (row tiles) x ceil(column tiles / 8) items (bounds for the smallest tiles used)
@@ -72,8 +83,15 @@ static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
   w.tiles = (int32_t*)take(2 * tile_table_ints(d, T) * 4);
   w.h = take(rows * d.ffn * es);
   w.y = take(rows * d.hidden * es);
-  w.part = (float*)take(d.dtype == PRISM_BF16 && T <= kDecodeMaxTokens
-                            ? (size_t)kDecodeSplits * rows * d.hidden * 4 : 0);
+  // The decode-only regions are reserved for every T (sized for min(T, kDecodeMaxTokens)
+  // tokens), so that the total never shrinks as T grows: a workspace sized for max_tokens
+  // serves every smaller batch.
+  const size_t t_dec = (size_t)(T < kDecodeMaxTokens ? T : kDecodeMaxTokens);
+  const size_t rows_dec = t_dec * (size_t)(d.top_k + d.n_shared);
+  const bool bf16 = d.dtype == PRISM_BF16;
+  w.part = (float*)take(bf16 ? (size_t)kDecodeSplits * rows_dec * d.hidden * 4 : 0);
+  w.route_part = (double*)take(bf16 ? (size_t)ceil_div((int)t_dec, kRouteTokTile) * kRouteMaxHSplit *
+                                          route_col_tiles(d.n_experts) * 64 * 4 * 8 : 0);
   w.total = off;
   return w;
 }
@@ -95,18 +113,44 @@ prism_status launch_route(const prism_layer_desc& d, const void* x, const void* 
                           float* topk_gate, int32_t* counts, int64_t* counts_accum,
                           hipStream_t st);
 
-// inv may be NULL.
+// counts NULL: no activation counts from the router (launch_dispatch can supply them).
+// inv, counts, counts_accum of launch_dispatch may be NULL.
 prism_status launch_dispatch(const prism_layer_desc& d, const int32_t* topk_idx,
                              const uint8_t* mask, int T, int32_t* local_src,
                              int32_t* local_offsets, int32_t* remote_src, int32_t* remote_offsets,
                              int32_t* n_local_remote, int64_t* remote_bytes, int32_t* inv,
-                             int32_t* block_hist, hipStream_t st);
+                             int32_t* block_hist, int32_t* counts, int64_t* counts_accum,
+                             hipStream_t st);
 
+// schedules_built: the two schedules in tiles already exist (decode front end).
+// deferred_splits NULL: y holds the finished expert outputs.  Otherwise the decode path leaves
+// its down projection as *deferred_splits (> 0) fp32 contraction slices in part, y unwritten,
+// for launch_combine to sum; *deferred_splits == 0 means y is finished.
 prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
                                int32_t* tiles, float* part, hipStream_t st,
-                               void* const* stage_events);
+                               void* const* stage_events, int* deferred_splits,
+                               bool schedules_built = false);
+
+// True when launch_decode_front_end serves this layer shape and batch.
+bool decode_front_end_applies(const prism_layer_desc& d, int T);
+
+// Decode batches: router, placement split and both GEMM schedules in two launches.
+// Outputs as launch_route + launch_dispatch (+ the schedules in tiles); route_part is
+// scratch.  stage_events: ROUTE brackets the first launch, DISPATCH the second.
+prism_status launch_decode_front_end(const prism_layer_desc& d, const void* x, const void* w_router,
+                                     const float* bias, const uint8_t* mask, int T,
+                                     int32_t* topk_idx, float* topk_gate, int32_t* counts,
+                                     int64_t* counts_accum, int32_t* local_src,
+                                     int32_t* local_offsets, int32_t* remote_src,
+                                     int32_t* remote_offsets, int32_t* n_local_remote,
+                                     int64_t* remote_bytes, int32_t* inv, double* route_part,
+                                     int32_t* tiles, hipStream_t st, void* const* stage_events);
+
+// Tile shapes of the decode path's two grouped GEMMs (row tile, column tiles), which the
+// front end needs to build their schedules.
+void decode_schedule_shapes(const prism_layer_desc& d, int* bm1, int* nt1, int* bm2, int* nt2);
 
 // Records stage_events[2 * stage + end] on st when tracing is on and the pair is set.
 static inline void trace(void* const* ev, int stage, int end, hipStream_t st) {
@@ -121,12 +165,23 @@ prism_status launch_build_inverse(const prism_layer_desc& d, const int32_t* loca
                                   const int32_t* local_offsets, int T, int32_t* inv,
                                   hipStream_t st);
 
+// n_splits > 0: expert outputs are taken from the fp32 slices in part (bf16 layers only),
+// each element summed over the slices and rounded to bf16 as the finished y would hold it.
 prism_status launch_combine(const prism_layer_desc& d, const void* y, const int32_t* inv,
-                            const float* topk_gate, int T, void* out, hipStream_t st);
+                            const float* topk_gate, int T, void* out, hipStream_t st,
+                            const float* part = nullptr, int n_splits = 0);
 
 // ---------------------------------------------------------------------------
 // Device helpers.
 // ---------------------------------------------------------------------------
+// Workgroup barrier for data handed over in LDS only: waits for this wavefront's LDS
+// traffic but, unlike __syncthreads(), not for its outstanding global loads and stores.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
   return __uint_as_float((uint32_t)b << 16);
 }

@@ -16,7 +16,16 @@
 // The accumulator layout leaves each token's logits spread over one 16-lane
 // group, so the k best experts are picked right there with xor-shuffle
 // arg-max reductions over (logit, index) pairs, four tokens at a time.
+//
+// Decode batches (at most 64 tokens, bf16) have only 1..4 token tiles, which would
+// leave the router on 1..4 compute units.  There the hidden dimension is also
+// split over workgroups: route_kernel<PARTIAL> writes each workgroup's fp64 tile
+// to memory, and a single-workgroup kernel sums those in a fixed order, finishes
+// the routing and, being alone on the critical path anyway, goes on to do the
+// placement split and to build the work schedules of the two grouped GEMMs.
+#include "dispatch_device.h"
 #include "prism_internal.h"
+#include "schedule.h"
 
 namespace prism {
 namespace {
@@ -36,80 +45,18 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&v)[8]) {
   v[4] = bf16_lo(a.z); v[5] = bf16_hi(a.z); v[6] = bf16_lo(a.w); v[7] = bf16_hi(a.w);
 }
 
-// NT = number of 16-expert column tiles (E <= 16 * NT).
-template <typename TIn, int NT>
-__global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
-    const TIn* __restrict__ x, const TIn* __restrict__ w_router, const float* __restrict__ bias,
-    int T, int H, int E, int k, int bias_group_tokens, float* __restrict__ logits,
-    int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate, int32_t* __restrict__ counts,
-    unsigned long long* __restrict__ counts_accum) {
-  constexpr int EP = NT * 16;             // padded expert count
-  __shared__ int s_counts[EP];
-  extern __shared__ __align__(16) double s_part[];   // [kWavesPerBlock / 2][NT * 4][64]
-
+// From the complete fp64 logit tile of 16 tokens (held by one wavefront in the
+// accumulator layout of v_mfma_f64_16x16x4) to top-k indices and gates.  Run by one
+// whole wavefront.  s_counts (LDS, may be NULL) receives +1 per selected expert.
+template <int NT>
+__device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0,
+                                            const float* __restrict__ bias, int T, int E, int k,
+                                            int bias_group_tokens, float* __restrict__ logits,
+                                            int32_t* topk_idx, float* __restrict__ topk_gate,
+                                            int* s_counts) {
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
   const int r = lane & 15;
   const int q = lane >> 4;
-  const int tok0 = blockIdx.x * kTokPerBlock;
-
-  for (int e = threadIdx.x; e < EP; e += blockDim.x) s_counts[e] = 0;
-  __syncthreads();
-
-  // ---- router GEMM on the fp64 matrix cores --------------------------------
-  f64x4 acc[NT];
-#pragma unroll
-  for (int n = 0; n < NT; ++n) acc[n] = f64x4{0.0, 0.0, 0.0, 0.0};
-
-  const int t_load = min(tok0 + r, T - 1);
-  const TIn* xrow = x + (size_t)t_load * H;
-  const TIn* wrow[NT];
-#pragma unroll
-  for (int n = 0; n < NT; ++n) wrow[n] = w_router + (size_t)min(n * 16 + r, E - 1) * H;
-
-  // wavefront w takes the 32-element slices w, w + 8, w + 16, ... of the hidden dimension
-  for (int h0 = wave * 32; h0 < H; h0 += 32 * kWavesPerBlock) {
-    // H % 8 == 0, so a lane's 8-element chunk is entirely inside or outside;
-    // lanes past the end feed zeros (the MFMA itself is wave-wide).
-    const int h = h0 + q * 8;
-    const bool inside = h < H;
-    const int hl = inside ? h : 0;
-    float xa[8];
-    load8(xrow + hl, xa);
-    float wb[NT][8];
-#pragma unroll
-    for (int n = 0; n < NT; ++n) load8(wrow[n] + hl, wb[n]);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const double a = inside ? (double)xa[j] : 0.0;
-#pragma unroll
-      for (int n = 0; n < NT; ++n)
-        acc[n] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)wb[n][j], acc[n], 0, 0, 0);
-    }
-  }
-
-  // ---- sum the partial tiles: (1,3,5,7) -> (0,2,4,6), (2,6) -> (0,4), 4 -> 0 ----
-#pragma unroll
-  for (int step = 1; step < kWavesPerBlock; step <<= 1) {
-    const bool sender = (wave & (2 * step - 1)) == step;
-    const bool receiver = (wave & (2 * step - 1)) == 0;
-    double* slot = s_part + (size_t)(wave / (2 * step)) * (NT * 4 * 64);
-    if (sender) {
-#pragma unroll
-      for (int n = 0; n < NT; ++n)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) slot[(n * 4 + v) * 64 + lane] = acc[n][v];
-    }
-    __syncthreads();
-    if (receiver) {
-#pragma unroll
-      for (int n = 0; n < NT; ++n)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) acc[n][v] += slot[(n * 4 + v) * 64 + lane];
-    }
-    __syncthreads();
-  }
-  if (wave != 0) return;   // wavefront 0 holds the full sums (no barrier follows)
 
   // ---- one rounding to fp32, then the fp32 bias add --------------------------
   // Accumulator register v of lane (r, q) is token 4v + q, expert 16n + r.
@@ -172,9 +119,110 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
     if (r < k && t < T) {
       topk_idx[(size_t)t * k + r] = myidx;
       topk_gate[(size_t)t * k + r] = (float)(w / sum);
-      atomicAdd(&s_counts[myidx], 1);
+      if (s_counts != nullptr) atomicAdd(&s_counts[myidx], 1);
     }
   }
+}
+
+// NT = number of 16-expert column tiles (E <= 16 * NT).
+// PARTIAL: workgroup (tile, y) covers hidden elements [y h_span, (y + 1) h_span) only and
+// stores its fp64 tile to partial[tile][y][NT][64 lanes][4]; nothing else is written.
+template <typename TIn, int NT, bool PARTIAL>
+__global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
+    const TIn* __restrict__ x, const TIn* __restrict__ w_router, const float* __restrict__ bias,
+    int T, int H, int E, int k, int bias_group_tokens, float* __restrict__ logits,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate, int32_t* __restrict__ counts,
+    unsigned long long* __restrict__ counts_accum, int h_span, double* __restrict__ partial) {
+  constexpr int EP = NT * 16;             // padded expert count
+  __shared__ int s_counts[EP];
+  extern __shared__ __align__(16) double s_part[];   // [kWavesPerBlock / 2][NT * 4][64]
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int r = lane & 15;
+  const int q = lane >> 4;
+  const int tok0 = blockIdx.x * kTokPerBlock;
+
+  for (int e = threadIdx.x; e < EP; e += blockDim.x) s_counts[e] = 0;
+  __syncthreads();
+
+  // ---- router GEMM on the fp64 matrix cores --------------------------------
+  f64x4 acc[NT];
+#pragma unroll
+  for (int n = 0; n < NT; ++n) acc[n] = f64x4{0.0, 0.0, 0.0, 0.0};
+
+  const int t_load = min(tok0 + r, T - 1);
+  const TIn* xrow = x + (size_t)t_load * H;
+  const TIn* wrow[NT];
+#pragma unroll
+  for (int n = 0; n < NT; ++n) wrow[n] = w_router + (size_t)min(n * 16 + r, E - 1) * H;
+
+  // Wavefront w takes the 32-element slices w, w + 8, w + 16, ... of the hidden dimension,
+  // U slices per trip so that their loads are all in flight before the first MFMA waits.
+  // H % 8 == 0, so a lane's 8-element chunk is entirely inside or outside; lanes past the
+  // end feed zeros (the MFMA itself is wave-wide).
+  constexpr int U = PARTIAL ? 1 : NT <= 1 ? 8 : NT <= 2 ? 4 : NT <= 4 ? 2 : 1;
+  constexpr int kSliceStride = 32 * kWavesPerBlock;
+  const int h_begin = PARTIAL ? (int)blockIdx.y * h_span : 0;
+  const int h_end = PARTIAL ? min(H, h_begin + h_span) : H;
+  for (int h0 = h_begin + wave * 32; h0 < h_end; h0 += kSliceStride * U) {
+    float xa[U][8];
+    float wb[U][NT][8];
+    bool inside[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int h = h0 + u * kSliceStride + q * 8;
+      inside[u] = h < h_end;
+      const int hl = inside[u] ? h : 0;
+      load8(xrow + hl, xa[u]);
+#pragma unroll
+      for (int n = 0; n < NT; ++n) load8(wrow[n] + hl, wb[u][n]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const double a = inside[u] ? (double)xa[u][j] : 0.0;
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+          acc[n] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)wb[u][n][j], acc[n], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- sum the partial tiles: (1,3,5,7) -> (0,2,4,6), (2,6) -> (0,4), 4 -> 0 ----
+#pragma unroll
+  for (int step = 1; step < kWavesPerBlock; step <<= 1) {
+    const bool sender = (wave & (2 * step - 1)) == step;
+    const bool receiver = (wave & (2 * step - 1)) == 0;
+    double* slot = s_part + (size_t)(wave / (2 * step)) * (NT * 4 * 64);
+    if (sender) {
+#pragma unroll
+      for (int n = 0; n < NT; ++n)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) slot[(n * 4 + v) * 64 + lane] = acc[n][v];
+    }
+    __syncthreads();
+    if (receiver) {
+#pragma unroll
+      for (int n = 0; n < NT; ++n)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[n][v] += slot[(n * 4 + v) * 64 + lane];
+    }
+    __syncthreads();
+  }
+  if (wave != 0) return;   // wavefront 0 holds the full sums (no barrier follows)
+
+  if (PARTIAL) {
+    double* out = partial + ((size_t)blockIdx.x * gridDim.y + blockIdx.y) * (NT * 256);
+#pragma unroll
+    for (int n = 0; n < NT; ++n) *reinterpret_cast<f64x4*>(out + n * 256 + lane * 4) = acc[n];
+    return;
+  }
+
+  finish_tile<NT>(acc, tok0, bias, T, E, k, bias_group_tokens, logits, topk_idx, topk_gate,
+                  counts != nullptr ? s_counts : nullptr);
+  if (counts == nullptr) return;   // the caller derives the counts from the dispatch histogram
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // this wavefront's LDS atomics, then its reads
 
   // ---- per-expert activation counts -----------------------------------------
@@ -192,32 +240,98 @@ __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
   if (i < n) p[i] = v;
 }
 
+// Decode front end, second launch (one workgroup): sums the hidden-dimension slices of
+// every token tile in slice order (in place, into slice 0), finishes the routing (one wavefront per tile of 16
+// tokens, at most 4 tiles), then splits the T*k assignments by placement and builds the
+// schedules of the two grouped GEMMs.  The steps hand their results to each other
+// through memory, separated by workgroup barriers.
+constexpr int kFrontThreads = dispatch_dev::kThreads;
+template <int NT>
+__global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
+    double* partial, int n_hsplit, const float* __restrict__ bias, int T, int E,
+    int k, int S, int bias_group_tokens, int32_t* topk_idx, float* __restrict__ topk_gate,
+    const uint8_t* __restrict__ mask, const dispatch_dev::SplitOut o,
+    int32_t* __restrict__ local_src, int32_t* __restrict__ remote_src, int32_t* __restrict__ inv,
+    const gg::SchedParams p0, const gg::SchedParams p1) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int n_tiles = (T + kTokPerBlock - 1) / kTokPerBlock;
+  // Slice sums, all threads: element j of tile t (a 4-double vector of the NT * 64 that
+  // make a tile) is added up over the slices in slice order and left in slice 0's place.
+  for (int item = threadIdx.x; item < n_tiles * NT * 64; item += kFrontThreads) {
+    const int tile = item / (NT * 64), j = item % (NT * 64);
+    double* base = partial + (size_t)tile * n_hsplit * (NT * 256) + j * 4;
+    f64x4 part[kRouteMaxHSplit];
+#pragma unroll
+    for (int y = 0; y < kRouteMaxHSplit; ++y)   // slices past the end re-read the last one (unused)
+      part[y] = *reinterpret_cast<const f64x4*>(base + (size_t)min(y, n_hsplit - 1) * (NT * 256));
+    f64x4 sum = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int y = 0; y < kRouteMaxHSplit; ++y) {
+      const bool on = y < n_hsplit;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) sum[v] += on ? part[y][v] : 0.0;
+    }
+    *reinterpret_cast<f64x4*>(base) = sum;
+  }
+  __syncthreads();   // the sums are visible to the whole workgroup
+  for (int tile = wave; tile < n_tiles; tile += kFrontThreads / kWave) {
+    f64x4 acc[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+      acc[n] = *reinterpret_cast<const f64x4*>(partial + (size_t)tile * n_hsplit * (NT * 256) +
+                                               n * 256 + lane * 4);
+    finish_tile<NT>(acc, tile * kTokPerBlock, bias, T, E, k, bias_group_tokens, nullptr, topk_idx,
+                    topk_gate, nullptr);
+  }
+  __syncthreads();   // topk_idx is complete and visible to the whole workgroup
+  dispatch_dev::dispatch_scatter_block<true>(topk_idx, T * k, E, mask, nullptr, 0, o, local_src,
+                                             remote_src, inv);
+  __syncthreads();   // local_offsets (written by the split) is visible to the whole workgroup
+  const gg::SchedParams p[2] = {p0, p1};
+  gg::build_schedules_block<2>(o.local_offsets, E, S, T, T * k, p);
+}
+
+// Hidden elements per workgroup of the split router: a multiple of the 256 elements one
+// trip of the 8 wavefronts covers, at most kRouteMaxHSplit slices.
+inline int route_h_span(int H) { return 256 * ceil_div(H, 256 * kRouteMaxHSplit); }
+
 template <typename TIn>
 prism_status launch_typed(const prism_layer_desc& d, const void* x, const void* w, const float* bias,
                           int T, float* logits, int32_t* idx, float* gate, int32_t* counts,
-                          int64_t* accum, hipStream_t st) {
+                          int64_t* accum, double* partial, hipStream_t st) {
   const int E = d.n_experts;
-  const int nt = ceil_div(E, 16);
-  const dim3 grid(ceil_div(T, kTokPerBlock)), block(kWavesPerBlock * kWave);
+  const int nt = route_col_tiles(E);
+  const int h_span = route_h_span(d.hidden);
+  const dim3 grid(ceil_div(T, kTokPerBlock), partial != nullptr ? ceil_div(d.hidden, h_span) : 1);
+  const dim3 block(kWavesPerBlock * kWave);
   static bool attr_set = false;
   if (!attr_set) {   // the 256-expert tile needs 128 KiB of LDS for the partial sums
-    if (hipFuncSetAttribute((const void*)route_kernel<TIn, 16>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (kWavesPerBlock / 2) * 16 * 4 * 64 * 8) != hipSuccess)
+    const int bytes = (kWavesPerBlock / 2) * 16 * 4 * 64 * 8;
+    if (hipFuncSetAttribute((const void*)route_kernel<TIn, 16, false>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess ||
+        hipFuncSetAttribute((const void*)route_kernel<TIn, 16, true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
       return PRISM_ERR_LAUNCH;
     attr_set = true;
   }
-#define PRISM_ROUTE_CASE(NT)                                                                     \
-  hipLaunchKernelGGL((route_kernel<TIn, NT>), grid, block,                                      \
+#define PRISM_ROUTE_LAUNCH(NT, PARTIAL)                                                          \
+  hipLaunchKernelGGL((route_kernel<TIn, NT, PARTIAL>), grid, block,                              \
                      (size_t)(kWavesPerBlock / 2) * NT * 4 * 64 * 8, st, (const TIn*)x, (const TIn*)w,  \
                      bias, T, d.hidden, E, d.top_k, d.bias_group_tokens, logits, idx, gate,     \
-                     counts, (unsigned long long*)accum)
+                     counts, (unsigned long long*)accum, h_span, partial)
+#define PRISM_ROUTE_CASE(NT)                                                                     \
+  do {                                                                                           \
+    if (partial != nullptr) PRISM_ROUTE_LAUNCH(NT, true);                                        \
+    else PRISM_ROUTE_LAUNCH(NT, false);                                                          \
+  } while (0)
   if (nt <= 1) PRISM_ROUTE_CASE(1);
   else if (nt <= 2) PRISM_ROUTE_CASE(2);
   else if (nt <= 4) PRISM_ROUTE_CASE(4);
   else if (nt <= 8) PRISM_ROUTE_CASE(8);
   else PRISM_ROUTE_CASE(16);
 #undef PRISM_ROUTE_CASE
+#undef PRISM_ROUTE_LAUNCH
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;
 }
@@ -235,13 +349,58 @@ prism_status launch_route(const prism_layer_desc& d, const void* x, const void* 
                           const float* bias, int T, float* logits, int32_t* topk_idx,
                           float* topk_gate, int32_t* counts, int64_t* counts_accum,
                           hipStream_t st) {
-  PRISM_TRY(launch_fill_i32(counts, d.n_experts, 0, st));
+  if (counts != nullptr) PRISM_TRY(launch_fill_i32(counts, d.n_experts, 0, st));
   if (T == 0) return PRISM_OK;
   if (d.dtype == PRISM_F32)
     return launch_typed<float>(d, x, w_router, bias, T, logits, topk_idx, topk_gate, counts,
-                               counts_accum, st);
+                               counts_accum, nullptr, st);
   return launch_typed<uint16_t>(d, x, w_router, bias, T, logits, topk_idx, topk_gate, counts,
-                                counts_accum, st);
+                                counts_accum, nullptr, st);
+}
+
+bool decode_front_end_applies(const prism_layer_desc& d, int T) {
+  return d.dtype == PRISM_BF16 && T > 0 && T <= kDecodeMaxTokens;
+}
+
+prism_status launch_decode_front_end(const prism_layer_desc& d, const void* x, const void* w_router,
+                                     const float* bias, const uint8_t* mask, int T,
+                                     int32_t* topk_idx, float* topk_gate, int32_t* counts,
+                                     int64_t* counts_accum, int32_t* local_src,
+                                     int32_t* local_offsets, int32_t* remote_src,
+                                     int32_t* remote_offsets, int32_t* n_local_remote,
+                                     int64_t* remote_bytes, int32_t* inv, double* route_part,
+                                     int32_t* tiles, hipStream_t st, void* const* stage_events) {
+  if (!decode_front_end_applies(d, T) || T * d.top_k > kDispatchChunk) return PRISM_ERR_INVALID_ARG;
+  trace(stage_events, PRISM_STAGE_ROUTE, 0, st);
+  PRISM_TRY(launch_typed<uint16_t>(d, x, w_router, bias, T, nullptr, nullptr, nullptr, nullptr,
+                                   nullptr, route_part, st));
+  trace(stage_events, PRISM_STAGE_ROUTE, 1, st);
+
+  const int E = d.n_experts;
+  const int n_hsplit = ceil_div(d.hidden, route_h_span(d.hidden));
+  const dispatch_dev::SplitOut o{local_offsets, remote_offsets, n_local_remote, remote_bytes, counts,
+                                 (unsigned long long*)counts_accum, d.hidden * elem_size(d.dtype)};
+  int bm1, nt1, bm2, nt2;
+  decode_schedule_shapes(d, &bm1, &nt1, &bm2, &nt2);
+  const gg::SchedParams p0{bm1, nt1, gg::sched_capacity(d, T, bm1, nt1), tiles};
+  const gg::SchedParams p1{bm2, nt2, gg::sched_capacity(d, T, bm2, nt2),
+                           tiles + tile_table_ints(d, T)};
+  trace(stage_events, PRISM_STAGE_DISPATCH, 0, st);
+#define PRISM_FRONT_CASE(NT)                                                                     \
+  hipLaunchKernelGGL((decode_front_end_kernel<NT>), dim3(1), dim3(kFrontThreads), 0, st,        \
+                     route_part, n_hsplit, bias, T, E, d.top_k, d.n_shared,                     \
+                     d.bias_group_tokens, topk_idx, topk_gate, mask, o, local_src, remote_src,  \
+                     inv, p0, p1)
+  const int nt = route_col_tiles(E);
+  if (nt <= 1) PRISM_FRONT_CASE(1);
+  else if (nt <= 2) PRISM_FRONT_CASE(2);
+  else if (nt <= 4) PRISM_FRONT_CASE(4);
+  else if (nt <= 8) PRISM_FRONT_CASE(8);
+  else PRISM_FRONT_CASE(16);
+#undef PRISM_FRONT_CASE
+  PRISM_CHECK_LAUNCH();
+  trace(stage_events, PRISM_STAGE_DISPATCH, 1, st);
+  return PRISM_OK;
 }
 
 }  // namespace prism

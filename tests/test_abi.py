@@ -40,6 +40,14 @@ def test_workspace_bytes_grows_with_tokens_and_is_aligned():
     assert P.workspace_bytes(d, 0) > 0
 
 
+def test_workspace_for_max_tokens_serves_every_smaller_batch():
+    """prism_workspace_bytes never shrinks as T grows (also across the decode-path boundary)."""
+    for d in (P.make_desc(4096, 14336, 8, 2, 0, "bf16"), P.make_desc(2048, 1408, 60, 4, 4, "bf16"),
+              P.make_desc(64, 96, 4, 2, 1, "f32"), P.make_desc(1024, 256, 256, 8, 2, "bf16")):
+        sizes = [P.workspace_bytes(d, t) for t in (0, 1, 15, 16, 17, 63, 64, 65, 128, 1000, 4096)]
+        assert sizes == sorted(sizes), sizes
+
+
 @pytest.mark.parametrize("kw,status", [
     (dict(top_k=0), 1), (dict(top_k=9, n_experts=8), 1), (dict(n_experts=257), 2),
     (dict(top_k=9, n_experts=16), 2), (dict(hidden=100), 2), (dict(ffn=100), 2),

@@ -25,6 +25,12 @@ CASES = {
     "mixtral_decode_small": dict(name="cfg3_mixtral_decode", T=32, H=256, F=448),
     "finegrained_small": dict(name="cfg4_finegrained", T=700, H=128, F=192, bias_group_tokens=128),
     "dsv2_small": dict(name="cfg5_dsv2lite_migration", T=515, H=128, F=192),
+    # decode-sized batches of the wide-expert workloads (fused router/split/schedule front end)
+    "finegrained_decode": dict(name="cfg4_finegrained", T=48, H=320, F=192, bias_group_tokens=16),
+    "dsv2_decode": dict(name="cfg5_dsv2lite_migration", T=64, H=1024, F=256),
+    "dsv2_decode_ragged": dict(name="cfg5_dsv2lite_migration", T=37, H=4352, F=192, E=40,
+                               n_local=20, n_swapped=6),
+    "decode_one_token": dict(name="cfg3_mixtral_decode", T=1, H=256, F=448),
 }
 
 
