@@ -45,6 +45,37 @@ def read_traffic(workload: str):
     return None
 
 
+def measured_ceilings(torch, P):
+    """Second denominators measured on this very GPU: a pure bf16 MFMA loop (constant and
+    random operand values: the sustained clock depends on them) and a streaming HBM read."""
+    n_wg, iters = 1024, 4000
+    out = torch.empty(n_wg * 256, dtype=torch.float32, device="cuda")
+    res = {}
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    for name, ops in (("mfma_bf16_constant_operands_tflops",
+                       torch.full((n_wg * 256 * 16,), 1.5, dtype=torch.bfloat16, device="cuda")),
+                      ("mfma_bf16_random_operands_tflops",
+                       torch.randn(n_wg * 256 * 16, generator=gen, device="cuda").to(torch.bfloat16))):
+        P.prism_ceiling_mfma_bf16(ops, out, n_wg, iters)          # warm-up
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = sum(P.prism_ceiling_mfma_bf16(ops, out, n_wg, iters) for _ in range(3))
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    src = torch.zeros(4 << 30, dtype=torch.uint8, device="cuda")   # 16x the last-level cache
+    n_rd = 32768
+    sink = torch.empty(n_rd * 256 * 16, dtype=torch.uint8, device="cuda")
+    P.prism_ceiling_hbm_read(src, sink, n_rd)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    nbytes = sum(P.prism_ceiling_hbm_read(src, sink, n_rd) for _ in range(5))
+    e1.record()
+    torch.cuda.synchronize()
+    res["hbm_read_gbs"] = nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return res
+
+
 def cpu_baseline(inp, n_sample: int):
     """Time the CPU oracle, as it stands, on the first n_sample tokens of the workload."""
     from oracle import prism_oracle as O
@@ -75,6 +106,8 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--trace-all", action="store_true", help="also time every stage (stderr)")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured MFMA / HBM ceilings of this GPU")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1")
@@ -189,6 +222,12 @@ def main():
         "roofline": roofline,
         "layer_tflops": layer_flop / (ms_per_step * 1e-3) / 1e12,
     }
+    if not args.no_ceilings:
+        ceil = measured_ceilings(torch, P)
+        result["measured_ceilings"] = ceil
+        ref = ceil["hbm_read_gbs"] if decode else ceil["mfma_bf16_random_operands_tflops"]
+        roofline["frac_of_measured_ceiling"] = roofline["achieved"] / ref
+        log("[bench] measured ceilings: " + ", ".join(f"{k}={v:.1f}" for k, v in ceil.items()))
     if not args.no_cpu_baseline:
         n_sample = args.cpu_sample_tokens or (cfg.T if decode else 2048)
         result["cpu_baseline"] = cpu_baseline(inp, n_sample)

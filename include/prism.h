@@ -194,11 +194,14 @@ prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const 
  * is a HOST array of 2 * PRISM_N_STAGES hipEvent_t handles (as void*), or
  * NULL.  For stage s, if stage_events[2s] and stage_events[2s+1] are both
  * non-NULL, the first is recorded on `stream` right before and the second
- * right after that stage's kernels: the router kernel, the three dispatch
- * kernels, the gate/up grouped GEMM alone, the down grouped GEMM (with, for
- * decode-sized batches, the kernel that sums its contraction slices), the
- * combine kernel.  Nothing else differs from prism_moe_layer, which is this
- * call with stage_events == NULL.
+ * right after that stage's kernels: the router kernel, the dispatch kernels,
+ * the gate/up grouped GEMM alone, the down grouped GEMM, the combine kernel.
+ * For decode-sized bf16 batches (T <= 64) the work is cut differently: ROUTE
+ * is the router GEMM with the hidden dimension split over workgroups,
+ * DISPATCH the single-workgroup kernel that finishes the routing, does the
+ * placement split and builds the GEMM work lists, and COMBINE also sums the
+ * contraction slices of the down projection.  Nothing else differs from
+ * prism_moe_layer, which is this call with stage_events == NULL.
  */
 #define PRISM_STAGE_ROUTE 0
 #define PRISM_STAGE_DISPATCH 1
@@ -215,6 +218,31 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                                     int32_t* remote_offsets, int32_t* n_local_remote,
                                     int64_t* remote_bytes, void* workspace, size_t workspace_bytes,
                                     void* stream, void* const* stage_events);
+
+/*
+ * Measured ceilings for measurement harnesses (not steps of the method).  Both
+ * calls only enqueue one kernel on `stream`; the caller times it.
+ *
+ * prism_ceiling_mfma_bf16: n_workgroups workgroups of 256 threads each run
+ * `iters` iterations of 8 independent v_mfma_f32_32x32x16_bf16 per wavefront.
+ *   operands  device, 16-byte aligned, n_workgroups * 256 * 2 vectors of 8
+ *             bf16: thread i multiplies vector 2i by vector 2i+1 (the clock
+ *             the chip sustains depends on these values)
+ *   out       device, n_workgroups * 256 floats (written, keeps the loop alive)
+ *   flop      host, receives the floating-point operations of the launch
+ *
+ * prism_ceiling_hbm_read: n_workgroups workgroups of 256 threads read `bytes`
+ * bytes (a multiple of 16 is read; use a buffer larger than the 256 MB
+ * last-level cache) with 16-byte loads, grid-strided.  Thread i stores the xor
+ * of the vectors it read to out[i] only when that xor is not zero, so an
+ * all-zero source is read without any write traffic.
+ *   src  device, 16-byte aligned;  out  device, n_workgroups * 256 * 16 bytes
+ * Errors: PRISM_ERR_INVALID_ARG for NULL or misaligned pointers, counts < 1.
+ */
+prism_status prism_ceiling_mfma_bf16(const void* operands, float* out, int32_t n_workgroups,
+                                     int32_t iters, double* flop, void* stream);
+prism_status prism_ceiling_hbm_read(const void* src, size_t bytes, void* out, int32_t n_workgroups,
+                                    void* stream);
 
 #ifdef __cplusplus
 }

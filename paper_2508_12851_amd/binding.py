@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_PKG, "libprism.so")
 
 PRISM_F32, PRISM_BF16 = 0, 1
 SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism_dispatch",
-           "prism_expert_ffn", "prism_combine", "prism_moe_layer", "prism_moe_layer_traced")
+           "prism_expert_ffn", "prism_combine", "prism_moe_layer", "prism_moe_layer_traced",
+           "prism_ceiling_mfma_bf16", "prism_ceiling_hbm_read")
 STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
 
 
@@ -65,6 +66,12 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.prism_moe_layer.argtypes = [dp, vp, vp, vp, wp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                     vp, sz, vp]
     lib.prism_moe_layer_traced.argtypes = lib.prism_moe_layer.argtypes + [vp]
+    lib.prism_ceiling_mfma_bf16.argtypes = [vp, vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
+    lib.prism_ceiling_hbm_read.argtypes = [vp, sz, vp, i32, vp]
+    for name in SYMBOLS:
+        # without argtypes ctypes would pass a device address as a 32-bit int
+        if getattr(lib, name).argtypes is None:
+            raise PrismError(f"binding bug: no argument types declared for {name}")
     for name in SYMBOLS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -254,3 +261,21 @@ def prism_moe_layer(desc: LayerDesc, x, w_router, router_bias, weights: WeightTa
                                           _ptr(workspace), workspace.numel(), _stream(stream)),
            "prism_moe_layer")
     return o
+
+
+def prism_ceiling_mfma_bf16(operands, out, n_workgroups: int, iters: int, stream=None) -> float:
+    """Enqueues the pure-MFMA loop (see prism.h); returns the flop count of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(load_library().prism_ceiling_mfma_bf16(_ptr(operands), _ptr(out), n_workgroups, iters,
+                                                  ctypes.byref(flop), _stream(stream)),
+           "prism_ceiling_mfma_bf16")
+    return flop.value
+
+
+def prism_ceiling_hbm_read(src, out, n_workgroups: int, stream=None) -> int:
+    """Enqueues the streaming read of all of src (see prism.h); returns the bytes read."""
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().prism_ceiling_hbm_read(_ptr(src), ctypes.c_size_t(nbytes), _ptr(out),
+                                                 n_workgroups, _stream(stream)),
+           "prism_ceiling_hbm_read")
+    return nbytes // 16 * 16

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "prism.h")).read()
-    return sorted(set(re.findall(r"\b(prism_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(prism_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported():
@@ -22,6 +22,13 @@ def test_header_symbols_are_exported():
     assert sorted(P.SYMBOLS) == declared
     for name in declared:
         assert hasattr(lib, name), name
+
+
+def test_every_entry_point_has_declared_argument_types():
+    """A ctypes call without argtypes would truncate 64-bit device addresses."""
+    lib = P.load_library()
+    for name in P.SYMBOLS:
+        assert getattr(lib, name).argtypes is not None, name
 
 
 def test_status_strings():
