@@ -56,3 +56,29 @@ def rel_err(a, ref):
 
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def run_layer(cfg, inp, mask=None, wt=None, ws=None, **kw):
+    desc = desc_of(cfg)
+    ws = P.alloc_workspace(desc, cfg.T) if ws is None else ws
+    mask = inp.mask if mask is None else mask
+    wt = weight_table(inp, mask) if wt is None else wt
+    o = P.prism_moe_layer(desc, to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias), wt,
+                          to_dev(mask), ws, **kw)
+    torch.cuda.synchronize()
+    return o
+
+
+def check_layer(cfg, o, ref):
+    """Integer outputs bit-exact, gates to 1e-6, layer output within the dtype's tolerance."""
+    nl, nr = o.n_local_remote.cpu().tolist()
+    assert np.array_equal(o.topk_idx.cpu().numpy(), ref.route.topk_idx)
+    assert np.array_equal(o.counts.cpu().numpy(), ref.route.counts)
+    assert np.max(np.abs(o.topk_gate.cpu().numpy() - ref.route.topk_gate), initial=0.0) <= 1e-6
+    assert (nl, nr) == (ref.dispatch.n_local, ref.dispatch.n_remote)
+    assert np.array_equal(o.remote_src.cpu().numpy()[:nr], ref.dispatch.remote_src)
+    assert np.array_equal(o.remote_offsets.cpu().numpy(), ref.dispatch.remote_offsets)
+    assert np.array_equal(o.remote_bytes.cpu().numpy(), ref.dispatch.remote_bytes)
+    err = rel_err(to_f32(o.out), ref.out)
+    assert err <= TOL[cfg.dtype], err
+    return err

@@ -1,0 +1,101 @@
+"""GPU parity at the edges of the launch configurations: batch sizes around the decode /
+prefill switch and around the tile heights, the shortest contractions the tile rings
+accept, one expert taking every token, a non-default stream with accumulated counts and
+stage events, and a workspace sized for a larger batch."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2508_12851_amd as P
+from prism_inputs import make_config, make_inputs
+
+from gpu_util import check_layer, desc_of, oracle_layer, run_layer, to_dev, weight_table
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("T", [2, 15, 16, 17, 63, 64, 65, 255, 256, 257, 513])
+def test_batch_sizes_around_tile_and_path_boundaries(T):
+    cfg = make_config("cfg2_mixtral_prefill", T=T, H=256, F=448)
+    inp = make_inputs(cfg)
+    err = check_layer(cfg, run_layer(cfg, inp), oracle_layer(inp))
+    print(f"T={T}: out err {err:.3g}")
+
+
+@pytest.mark.parametrize("T", [24, 300])
+@pytest.mark.parametrize("H,F", [(64, 64), (128, 64), (64, 192), (192, 128), (128, 1024)])
+def test_shortest_contractions(T, H, F):
+    """H or F of 64..192: the k-tile ring is as long as the whole contraction."""
+    cfg = make_config("cfg4_finegrained", T=T, H=H, F=F, E=12, k=3, S=1, n_local=7,
+                      bias_group_tokens=0)
+    inp = make_inputs(cfg)
+    err = check_layer(cfg, run_layer(cfg, inp), oracle_layer(inp))
+    print(f"T={T} H={H} F={F}: out err {err:.3g}")
+
+
+@pytest.mark.parametrize("T", [40, 700])
+def test_one_expert_takes_every_token(T):
+    """A +1000 bias sends slot 0 of every token to expert 3: one group with T rows (several
+    row tiles), the other hosted experts nearly empty."""
+    cfg = make_config("cfg2_mixtral_prefill", T=T, H=256, F=448)
+    inp = make_inputs(cfg)
+    inp.bias[:, 3] += 1000.0
+    inp.mask[3] = 1
+    o = run_layer(cfg, inp)
+    check_layer(cfg, o, oracle_layer(inp))
+    assert int(o.counts[3]) == T and torch.all(o.topk_idx[:, 0] == 3)
+
+
+def test_other_stream_accumulated_counts_and_stage_events():
+    cfg = make_config("cfg5_dsv2lite_migration", T=300, H=128, F=192)
+    inp = make_inputs(cfg)
+    ref = oracle_layer(inp)
+    desc = desc_of(cfg)
+    ws = P.alloc_workspace(desc, cfg.T)
+    wt = weight_table(inp)
+    args = (desc, to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias), wt, to_dev(inp.mask), ws)
+    accum = torch.zeros(cfg.E, dtype=torch.int64, device="cuda")
+    n_st = len(P.STAGES)
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * n_st)]
+    handles = (ctypes.c_void_p * (2 * n_st))()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for i, ev in enumerate(events):
+            ev.record()                      # materialise the hipEvent_t
+            handles[i] = ev.cuda_event
+        o = None
+        for _ in range(3):
+            o = P.prism_moe_layer(*args, counts_accum=accum, stream=side, stage_events=handles)
+    side.synchronize()
+    check_layer(cfg, o, ref)
+    assert np.array_equal(accum.cpu().numpy(), 3 * ref.route.counts.astype(np.int64))
+    # stages were recorded in launch order on that stream: every interval is >= 0
+    for s in range(n_st):
+        assert events[2 * s].elapsed_time(events[2 * s + 1]) >= 0.0
+        if s:
+            assert events[2 * s - 1].elapsed_time(events[2 * s]) >= 0.0
+
+
+@pytest.mark.parametrize("T", [20, 300])
+def test_workspace_sized_for_a_larger_batch(T):
+    cfg = make_config("cfg4_finegrained", T=T, H=128, F=192, bias_group_tokens=64)
+    inp = make_inputs(cfg)
+    ws = P.alloc_workspace(desc_of(cfg), 2048)
+    ws.fill_(0xA5)
+    check_layer(cfg, run_layer(cfg, inp, ws=ws), oracle_layer(inp))
+
+
+def test_unsupported_shapes_and_small_workspaces_are_refused_before_any_launch():
+    with pytest.raises(P.PrismError, match="supported limits"):
+        P.workspace_bytes(P.make_desc(96, 128, 8, 2, 0, "bf16"), 16)      # H % 64 != 0 (bf16 FFN)
+    d = P.make_desc(128, 128, 8, 2, 0, "bf16")
+    small = P.alloc_workspace(d, 4)
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    hosted = [tuple(torch.zeros(s, **bf) for s in ((128, 128), (128, 128), (128, 128)))] * 8
+    with pytest.raises(P.PrismError, match="workspace too small"):
+        P.prism_moe_layer(d, torch.zeros((4096, 128), **bf), torch.zeros((8, 128), **bf), None,
+                          P.WeightTable(hosted, []), torch.ones(8, dtype=torch.uint8, device="cuda"),
+                          small)

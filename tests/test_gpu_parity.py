@@ -12,7 +12,8 @@ import paper_2508_12851_amd as P
 from oracle import prism_oracle as O
 from prism_inputs import make_config, make_inputs
 
-from gpu_util import TOL, desc_of, oracle_layer, rel_err, to_dev, to_f32, weight_table
+from gpu_util import (TOL, check_layer as _check_layer, desc_of, oracle_layer, rel_err,
+                      run_layer as _run_layer, to_dev, to_f32, weight_table)
 
 pytestmark = pytest.mark.gpu
 
@@ -191,31 +192,6 @@ def test_expert_ffn_and_combine_parity(case):
 # ---------------------------------------------------------------------------
 # the whole layer
 # ---------------------------------------------------------------------------
-
-def _run_layer(cfg, inp, mask=None, wt=None):
-    desc = desc_of(cfg)
-    ws = P.alloc_workspace(desc, cfg.T)
-    mask = inp.mask if mask is None else mask
-    wt = weight_table(inp, mask) if wt is None else wt
-    o = P.prism_moe_layer(desc, to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias), wt,
-                          to_dev(mask), ws)
-    torch.cuda.synchronize()
-    return o
-
-
-def _check_layer(cfg, o, ref):
-    nl, nr = o.n_local_remote.cpu().tolist()
-    assert np.array_equal(o.topk_idx.cpu().numpy(), ref.route.topk_idx)
-    assert np.array_equal(o.counts.cpu().numpy(), ref.route.counts)
-    assert np.max(np.abs(o.topk_gate.cpu().numpy() - ref.route.topk_gate)) <= 1e-6
-    assert (nl, nr) == (ref.dispatch.n_local, ref.dispatch.n_remote)
-    assert np.array_equal(o.remote_src.cpu().numpy()[:nr], ref.dispatch.remote_src)
-    assert np.array_equal(o.remote_offsets.cpu().numpy(), ref.dispatch.remote_offsets)
-    assert np.array_equal(o.remote_bytes.cpu().numpy(), ref.dispatch.remote_bytes)
-    err = rel_err(to_f32(o.out), ref.out)
-    assert err <= TOL[cfg.dtype], err
-    return err
-
 
 @pytest.mark.parametrize("case", list(CASES))
 def test_moe_layer_parity(case):
