@@ -32,6 +32,9 @@ CASES = {
     "dsv2_decode_ragged": dict(name="cfg5_dsv2lite_migration", T=37, H=4352, F=192, E=40,
                                n_local=20, n_swapped=6),
     "decode_one_token": dict(name="cfg3_mixtral_decode", T=1, H=256, F=448),
+    # few big experts: the 256-row tile configuration (several row tiles and a ragged last one)
+    "two_big_experts": dict(name="cfg2_mixtral_prefill", T=1100, H=256, F=448, E=2, k=2, n_local=1),
+    "three_big_experts": dict(name="cfg2_mixtral_prefill", T=1500, H=192, F=320, E=3, k=2, n_local=2),
 }
 
 
