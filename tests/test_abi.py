@@ -1,4 +1,4 @@
-"""The C-ABI library builds, loads and exports every symbol include/prism.h declares;
+"""The C-ABI library builds, loads and exports every symbol include/*.h declares;
 host-side validation returns error codes (no kernel is launched in these tests)."""
 import ctypes
 import os
@@ -11,16 +11,18 @@ import paper_2508_12851_amd as P
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "prism.h")).read()
+def _declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     return sorted(set(re.findall(r"\b(prism_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported():
+    from paper_2508_12851_amd.placement import PLACEMENT_SYMBOLS
     lib = P.load_library()
-    declared = _declared_symbols()
-    assert sorted(P.SYMBOLS) == declared
-    for name in declared:
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["prism.h", "prism_placement.h"]
+    assert sorted(P.SYMBOLS) == _declared_symbols("prism.h")
+    assert sorted(PLACEMENT_SYMBOLS) == _declared_symbols("prism_placement.h")
+    for name in _declared_symbols("prism.h") + _declared_symbols("prism_placement.h"):
         assert hasattr(lib, name), name
 
 
