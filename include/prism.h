@@ -177,6 +177,34 @@ prism_status prism_combine(const prism_layer_desc* desc, const void* y, const in
                            void* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The two ends of the remote call on the requesting server (Sec. III-A: "a
+ * remote call is initiated ... the results of experts are transmitted back ...
+ * where they are aggregated"; Sec. III-B: what travels is the activation).
+ *
+ * prism_pack_remote gathers the activation rows to ship, in remote-list order:
+ *   packed[r] = x[remote_src[r] / k]  for r < remote_offsets[E]
+ *   packed [T*k, H] layer dtype (rows past the remote count untouched).
+ * Segment remote_offsets[e]..[e+1] of packed is what the server hosting expert
+ * e receives; that server runs prism_expert_ffn on it (top_k = 1, no shared
+ * experts, local_src = 0..R-1, local_offsets = the received segment sizes).
+ *
+ * prism_combine_remote adds the returned rows to the local partial sum:
+ *   out[t] = out[t] + sum over remote slots j (ascending) of
+ *            topk_gate[t,j] * y_remote[row of (t,j) in the remote list]
+ * in fp32, rounded once more to the layer dtype; with prism_moe_layer's out it
+ * completes the layer (= the layer with every expert hosted, up to rounding).
+ *   y_remote [>= R, H] layer dtype, rows in remote-list order;  out [T,H] in/out.
+ * The workspace is used for the inverse of the remote list (do not run it
+ * concurrently with another call on the same workspace).
+ */
+prism_status prism_pack_remote(const prism_layer_desc* desc, const void* x, const int32_t* remote_src,
+                               const int32_t* remote_offsets, int32_t T, void* packed, void* stream);
+prism_status prism_combine_remote(const prism_layer_desc* desc, const void* y_remote,
+                                  const int32_t* remote_src, const int32_t* remote_offsets,
+                                  const float* topk_gate, int32_t T, void* out, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
+/*
  * The whole layer: route -> dispatch -> expert FFN -> combine, on one stream,
  * with no host synchronisation.  Outputs as in the calls above; local_src,
  * local_offsets, the FFN intermediate and y live in the workspace.

@@ -28,6 +28,11 @@ standard definitions of the two model families it evaluates, Sec. IV):
   combine    out[t] = sum_{local slots j} gate[t,j] * y[(t,j)] + sum_s y_sh[s,t]
              ("results of experts are ... aggregated", Sec. III-A); remote
              slots contribute nothing here (their rows arrive later).
+  pack_remote / combine_remote
+             the two ends of the remote call: the activation rows shipped for the
+             remote list, and the returned expert outputs added, gate-weighted, to
+             the local partial sum.  The hosting server's part in between is
+             expert_ffn on the shipped rows.
 
 All floating point is fp64 except where stated; the only roundings are the
 fp32 logit (+ fp32 bias add), the fp32 gates and the final output rounding to
@@ -50,7 +55,8 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 __all__ = [
-    "route", "dispatch", "expert_ffn", "combine", "moe_layer", "swiglu_rows",
+    "route", "dispatch", "expert_ffn", "combine", "moe_layer", "swiglu_rows", "pack_remote",
+    "combine_remote",
     "round_to_dtype", "RouteResult", "DispatchResult", "LayerResult",
 ]
 
@@ -224,6 +230,35 @@ def combine(y: np.ndarray, local_src: np.ndarray, topk_gate: np.ndarray, T: int,
                 out[t] += float(topk_gate[t, j]) * y[r]
         for s in range(n_shared):
             out[t] += y[n_local + s * T + t]
+    return round_to_dtype(out, dtype)
+
+
+# ---------------------------------------------------------------------------
+# the remote call (Sec. III-A: a remote call is initiated, "the results of experts
+# are transmitted back ... where they are aggregated"; Sec. III-B: what is shipped
+# is the activation, the hosting server executes the expert, results come back)
+# ---------------------------------------------------------------------------
+
+def pack_remote(x: np.ndarray, remote_src: np.ndarray, k: int) -> np.ndarray:
+    """The activation rows shipped to the hosting servers: row r is the token of remote
+    assignment remote_src[r] (flat id t*k + j), in remote-list order."""
+    return np.stack([x[int(a) // k] for a in remote_src]) if len(remote_src) else \
+        np.zeros((0, x.shape[1]), dtype=x.dtype)
+
+
+def combine_remote(out_local: np.ndarray, y_remote: np.ndarray, remote_src: np.ndarray,
+                   topk_gate: np.ndarray, dtype: str) -> np.ndarray:
+    """Adds the returned expert outputs to the local partial sum:
+    out[t] = out_local[t] + sum over remote slots (ascending j) of gate[t,j] * y_remote[row(t,j)],
+    rounded once more to the layer dtype.  y_remote [R, H] is in remote-list order."""
+    k = topk_gate.shape[1]
+    out = np.array(out_local, dtype=np.float64)
+    row_of = {int(a): r for r, a in enumerate(remote_src)}
+    for t in range(out.shape[0]):
+        for j in range(k):
+            r = row_of.get(t * k + j)
+            if r is not None:
+                out[t] += float(topk_gate[t, j]) * y_remote[r]
     return round_to_dtype(out, dtype)
 
 

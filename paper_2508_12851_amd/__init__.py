@@ -6,5 +6,5 @@ from .binding import (  # noqa: F401
     ExpertWeights, LayerDesc, LayerOut, PrismError, WeightTable, alloc_layer_out, alloc_workspace,
     load_library, make_desc, prism_combine, prism_dispatch, prism_expert_ffn, prism_moe_layer,
     prism_route, torch_dtype, workspace_bytes, LIB_PATH, SYMBOLS, STAGES,
-    prism_ceiling_mfma_bf16, prism_ceiling_hbm_read,
+    prism_ceiling_mfma_bf16, prism_ceiling_hbm_read, prism_pack_remote, prism_combine_remote,
 )

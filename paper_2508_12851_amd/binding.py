@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_PKG, "libprism.so")
 PRISM_F32, PRISM_BF16 = 0, 1
 SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism_dispatch",
            "prism_expert_ffn", "prism_combine", "prism_moe_layer", "prism_moe_layer_traced",
-           "prism_ceiling_mfma_bf16", "prism_ceiling_hbm_read")
+           "prism_ceiling_mfma_bf16", "prism_ceiling_hbm_read", "prism_pack_remote",
+           "prism_combine_remote")
 STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
 
 
@@ -66,6 +67,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.prism_moe_layer.argtypes = [dp, vp, vp, vp, wp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                     vp, sz, vp]
     lib.prism_moe_layer_traced.argtypes = lib.prism_moe_layer.argtypes + [vp]
+    lib.prism_pack_remote.argtypes = [dp, vp, vp, vp, i32, vp, vp]
+    lib.prism_combine_remote.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.prism_ceiling_mfma_bf16.argtypes = [vp, vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.prism_ceiling_hbm_read.argtypes = [vp, sz, vp, i32, vp]
     for name in SYMBOLS:
@@ -279,3 +282,24 @@ def prism_ceiling_hbm_read(src, out, n_workgroups: int, stream=None) -> int:
                                                  n_workgroups, _stream(stream)),
            "prism_ceiling_hbm_read")
     return nbytes // 16 * 16
+
+
+def prism_pack_remote(desc: LayerDesc, x, remote_src, remote_offsets, stream=None) -> torch.Tensor:
+    """Activation rows to ship, in remote-list order ([T*k, H]; rows past the remote count are zero)."""
+    T = x.shape[0]
+    packed = torch.zeros((T * desc.top_k, desc.hidden), dtype=x.dtype, device=x.device)
+    _check(load_library().prism_pack_remote(ctypes.byref(desc), _ptr(x), _ptr(remote_src),
+                                            _ptr(remote_offsets), T, _ptr(packed), _stream(stream)),
+           "prism_pack_remote")
+    return packed
+
+
+def prism_combine_remote(desc: LayerDesc, y_remote, remote_src, remote_offsets, topk_gate, out,
+                         workspace, stream=None) -> torch.Tensor:
+    """Adds the returned expert outputs (remote-list order) into out, in place."""
+    T = topk_gate.shape[0]
+    _check(load_library().prism_combine_remote(ctypes.byref(desc), _ptr(y_remote), _ptr(remote_src),
+                                               _ptr(remote_offsets), _ptr(topk_gate), T, _ptr(out),
+                                               _ptr(workspace), workspace.numel(), _stream(stream)),
+           "prism_combine_remote")
+    return out

@@ -130,6 +130,30 @@ prism_status prism_combine(const prism_layer_desc* desc, const void* y, const in
   return launch_combine(*desc, y, ws.inv, topk_gate, T, out, st);
 }
 
+prism_status prism_pack_remote(const prism_layer_desc* desc, const void* x, const int32_t* remote_src,
+                               const int32_t* remote_offsets, int32_t T, void* packed, void* stream) {
+  PRISM_TRY(validate_desc(desc, T, false));
+  PRISM_RETURN_IF(remote_offsets == nullptr, PRISM_ERR_INVALID_ARG);
+  if (T > 0) PRISM_RETURN_IF(x == nullptr || remote_src == nullptr || packed == nullptr, PRISM_ERR_INVALID_ARG);
+  return launch_pack_rows(*desc, x, remote_src, remote_offsets, T, packed, (hipStream_t)stream);
+}
+
+prism_status prism_combine_remote(const prism_layer_desc* desc, const void* y_remote,
+                                  const int32_t* remote_src, const int32_t* remote_offsets,
+                                  const float* topk_gate, int32_t T, void* out, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  PRISM_TRY(validate_desc(desc, T, false));
+  PRISM_RETURN_IF(remote_offsets == nullptr, PRISM_ERR_INVALID_ARG);
+  if (T > 0)
+    PRISM_RETURN_IF(y_remote == nullptr || remote_src == nullptr || topk_gate == nullptr || out == nullptr,
+                    PRISM_ERR_INVALID_ARG);
+  Workspace ws;
+  PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
+  const hipStream_t st = (hipStream_t)stream;
+  PRISM_TRY(launch_build_inverse(*desc, remote_src, remote_offsets, T, ws.inv, st));
+  return launch_combine(*desc, y_remote, ws.inv, topk_gate, T, out, st, nullptr, 0, true);
+}
+
 prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                                     const void* w_router, const float* router_bias,
                                     const prism_expert_weights* weights,

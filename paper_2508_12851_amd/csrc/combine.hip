@@ -25,6 +25,7 @@ __global__ void scatter_inverse_kernel(const int32_t* __restrict__ local_src,
 template <typename T> struct Vec;
 template <> struct Vec<float> {
   static constexpr int N = 4;
+  typedef f32x4 raw;
   __device__ static void load(const float* p, float (&v)[N]) {
     const f32x4 a = *reinterpret_cast<const f32x4*>(p);
     v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3];
@@ -35,6 +36,7 @@ template <> struct Vec<float> {
 };
 template <> struct Vec<uint16_t> {
   static constexpr int N = 8;
+  typedef uint4 raw;
   __device__ static void load(const uint16_t* p, float (&v)[N]) {
     const uint4 a = *reinterpret_cast<const uint4*>(p);
     v[0] = bf16_lo(a.x); v[1] = bf16_hi(a.x); v[2] = bf16_lo(a.y); v[3] = bf16_hi(a.y);
@@ -48,11 +50,13 @@ template <> struct Vec<uint16_t> {
   }
 };
 
-template <typename TIO>
+// ADD: the sum starts from the value out already holds (returned remote rows are added to
+// the local partial sum) instead of zero.
+template <typename TIO, bool ADD>
 __global__ __launch_bounds__(256) void combine_kernel(const TIO* __restrict__ y,
                                                       const int32_t* __restrict__ inv,
                                                       const float* __restrict__ gate, int T, int H,
-                                                      int k, int S, TIO* __restrict__ out) {
+                                                      int k, int S, TIO* out) {
   constexpr int N = Vec<TIO>::N;
   const int vec_per_row = H / N;
   const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -60,8 +64,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const TIO* __restrict__ y,
   const int t = (int)(gid / vec_per_row);
   const int col = (int)(gid - (long long)t * vec_per_row) * N;
   float acc[N];
+  if (ADD) {
+    Vec<TIO>::load(out + (size_t)t * H + col, acc);
+  } else {
 #pragma unroll
-  for (int i = 0; i < N; ++i) acc[i] = 0.f;
+    for (int i = 0; i < N; ++i) acc[i] = 0.f;
+  }
   for (int j = 0; j < k; ++j) {
     const int row = inv[t * k + j];
     if (row >= 0) {
@@ -80,6 +88,26 @@ __global__ __launch_bounds__(256) void combine_kernel(const TIO* __restrict__ y,
     for (int i = 0; i < N; ++i) acc[i] += v[i];
   }
   Vec<TIO>::store(out + (size_t)t * H + col, acc);
+}
+
+// Shipped activation rows of the remote list: packed[r] = x[src[r] / k] for r < offsets[E].
+template <typename TIO>
+__global__ __launch_bounds__(256) void pack_rows_kernel(const TIO* __restrict__ x,
+                                                        const int32_t* __restrict__ src,
+                                                        const int32_t* __restrict__ offsets, int E,
+                                                        int k, int H, int max_rows,
+                                                        TIO* __restrict__ packed) {
+  constexpr int N = Vec<TIO>::N;
+  const int vec_per_row = H / N;
+  const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long long)max_rows * vec_per_row) return;
+  const int r = (int)(gid / vec_per_row);
+  if (r >= offsets[E]) return;
+  const int col = (int)(gid - (long long)r * vec_per_row) * N;
+  const int t = src[r] / k;
+  typedef typename Vec<TIO>::raw raw_t;
+  *reinterpret_cast<raw_t*>(packed + (size_t)r * H + col) =
+      *reinterpret_cast<const raw_t*>(x + (size_t)t * H + col);
 }
 
 // Same aggregation with y taken from the contraction slices (bf16 layers).  Four
@@ -173,10 +201,42 @@ prism_status launch_build_inverse(const prism_layer_desc& d, const int32_t* loca
   return PRISM_OK;
 }
 
+prism_status launch_pack_rows(const prism_layer_desc& d, const void* x, const int32_t* src,
+                              const int32_t* offsets, int T, void* packed, hipStream_t st) {
+  const int A = T * d.top_k;
+  if (A == 0) return PRISM_OK;
+  const int n = d.dtype == PRISM_F32 ? 4 : 8;
+  const long long threads = (long long)A * (d.hidden / n);
+  const unsigned blocks = (unsigned)((threads + 255) / 256);
+  if (d.dtype == PRISM_F32)
+    hipLaunchKernelGGL(pack_rows_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)x, src,
+                       offsets, d.n_experts, d.top_k, d.hidden, A, (float*)packed);
+  else
+    hipLaunchKernelGGL(pack_rows_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st,
+                       (const uint16_t*)x, src, offsets, d.n_experts, d.top_k, d.hidden, A,
+                       (uint16_t*)packed);
+  PRISM_CHECK_LAUNCH();
+  return PRISM_OK;
+}
+
 prism_status launch_combine(const prism_layer_desc& d, const void* y, const int32_t* inv,
                             const float* topk_gate, int T, void* out, hipStream_t st,
-                            const float* part, int n_splits) {
+                            const float* part, int n_splits, bool add_to_out) {
   if (T == 0) return PRISM_OK;
+  if (add_to_out) {   // returned remote rows: no shared experts, no slices
+    if (n_splits > 0) return PRISM_ERR_INVALID_ARG;
+    const int nv = d.dtype == PRISM_F32 ? 4 : 8;
+    const long long th = (long long)T * (d.hidden / nv);
+    const unsigned bl = (unsigned)((th + 255) / 256);
+    if (d.dtype == PRISM_F32)
+      hipLaunchKernelGGL((combine_kernel<float, true>), dim3(bl), dim3(256), 0, st, (const float*)y,
+                         inv, topk_gate, T, d.hidden, d.top_k, 0, (float*)out);
+    else
+      hipLaunchKernelGGL((combine_kernel<uint16_t, true>), dim3(bl), dim3(256), 0, st,
+                         (const uint16_t*)y, inv, topk_gate, T, d.hidden, d.top_k, 0, (uint16_t*)out);
+    PRISM_CHECK_LAUNCH();
+    return PRISM_OK;
+  }
   if (n_splits > 0 && (d.dtype != PRISM_BF16 || part == nullptr || n_splits > kDecodeSplits))
     return PRISM_ERR_INVALID_ARG;
   if (n_splits > 0) {
@@ -191,10 +251,10 @@ prism_status launch_combine(const prism_layer_desc& d, const void* y, const int3
   const long long threads = (long long)T * (d.hidden / n);
   const unsigned blocks = (unsigned)((threads + 255) / 256);
   if (d.dtype == PRISM_F32)
-    hipLaunchKernelGGL(combine_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)y, inv,
+    hipLaunchKernelGGL((combine_kernel<float, false>), dim3(blocks), dim3(256), 0, st, (const float*)y, inv,
                        topk_gate, T, d.hidden, d.top_k, d.n_shared, (float*)out);
   else
-    hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)y,
+    hipLaunchKernelGGL((combine_kernel<uint16_t, false>), dim3(blocks), dim3(256), 0, st, (const uint16_t*)y,
                        inv, topk_gate, T, d.hidden, d.top_k, d.n_shared, (uint16_t*)out);
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;

@@ -165,11 +165,16 @@ prism_status launch_build_inverse(const prism_layer_desc& d, const int32_t* loca
                                   const int32_t* local_offsets, int T, int32_t* inv,
                                   hipStream_t st);
 
+// add_to_out: the gate-weighted rows are added to what out holds (no shared rows, no slices).
 // n_splits > 0: expert outputs are taken from the fp32 slices in part (bf16 layers only),
 // each element summed over the slices and rounded to bf16 as the finished y would hold it.
 prism_status launch_combine(const prism_layer_desc& d, const void* y, const int32_t* inv,
                             const float* topk_gate, int T, void* out, hipStream_t st,
-                            const float* part = nullptr, int n_splits = 0);
+                            const float* part = nullptr, int n_splits = 0, bool add_to_out = false);
+
+// packed[r] = x[src[r] / k] for the rows r < offsets[E] of an assignment list.
+prism_status launch_pack_rows(const prism_layer_desc& d, const void* x, const int32_t* src,
+                              const int32_t* offsets, int T, void* packed, hipStream_t st);
 
 // ---------------------------------------------------------------------------
 // Device helpers.

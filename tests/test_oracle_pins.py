@@ -401,3 +401,37 @@ def test_bf16_layer_output_is_bf16_representable():
     inp = make_inputs(cfg, weights="all")
     out = _layer(inp).out
     assert np.array_equal(out, torch.from_numpy(out).to(torch.bfloat16).float().numpy())
+
+
+# ---------------------------------------------------------------------------
+# the remote call: ship rows, execute on the hosting server, add the returned rows
+# ---------------------------------------------------------------------------
+
+def test_remote_call_completes_the_layer():
+    """local partial + returned remote rows = the layer with every expert hosted (the dense
+    reference), and the shipped rows are the tokens of the remote assignments."""
+    rng = np.random.default_rng(21)
+    T, H, E, F, k, S = 23, 16, 6, 24, 3, 1
+    x = rng.standard_normal((T, H))
+    w_r = rng.standard_normal((E, H)) / 4
+    experts = [tuple(rng.standard_normal(s) / 4 for s in ((F, H), (F, H), (H, F))) for _ in range(E)]
+    shared = [tuple(rng.standard_normal(s) / 4 for s in ((F, H), (F, H), (H, F))) for _ in range(S)]
+    mask = np.array([1, 0, 1, 0, 0, 1], np.uint8)
+    part = O.moe_layer(x, w_r, None, lambda e: experts[e], shared, mask, k, "f32")
+    full = O.moe_layer(x, w_r, None, lambda e: experts[e], shared, np.ones(E, np.uint8), k, "f32")
+    d = part.dispatch
+    shipped = O.pack_remote(x, d.remote_src, k)
+    assert shipped.shape == (d.n_remote, H)
+    for r, a in enumerate(d.remote_src):
+        assert np.array_equal(shipped[r], x[a // k])
+    # hosting side: the same grouped FFN over the shipped rows (one slot per row, no shared experts)
+    y_remote = O.expert_ffn(shipped, lambda e: experts[e], [], np.arange(d.n_remote),
+                            d.remote_offsets, 1)
+    # ... equals running it on the requester's tokens through the remote list itself
+    y_direct = O.expert_ffn(x, lambda e: experts[e], [], d.remote_src, d.remote_offsets, k)
+    assert np.allclose(y_remote, y_direct, rtol=0, atol=1e-12)
+    done = O.combine_remote(part.out, y_remote, d.remote_src, part.route.topk_gate, "f32")
+    assert np.max(np.abs(done - full.out)) <= 1e-5 * (1 + np.max(np.abs(full.out)))
+    # nothing remote: nothing added
+    same = O.combine_remote(full.out, np.zeros((0, H)), np.zeros(0, np.int64), full.route.topk_gate, "f32")
+    assert np.array_equal(same, full.out)
