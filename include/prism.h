@@ -74,6 +74,14 @@ typedef enum { PRISM_F32 = 0, PRISM_BF16 = 1 } prism_dtype;
 #define PRISM_MAX_TOPK 8
 #define PRISM_MAX_SHARED 16
 
+/* Gate values of a token's k picks (the paper leaves the gating function open; the two
+ * model families of Sec. IV use one convention each).  The picks themselves, the counts
+ * and the split do not depend on it. */
+typedef enum {
+  PRISM_GATES_RENORMALIZED = 0, /* softmax over the k picked logits: the gates sum to 1 */
+  PRISM_GATES_SOFTMAX_ALL = 1   /* the picked entries of the softmax over all E logits */
+} prism_gate_mode;
+
 /* Layer description: plain data in HOST memory, passed by const pointer. */
 typedef struct {
   int32_t hidden;            /* H */
@@ -83,6 +91,7 @@ typedef struct {
   int32_t n_shared;          /* S always-on shared experts (hosted everywhere) */
   int32_t dtype;             /* prism_dtype of x, every weight matrix, y and out */
   int32_t bias_group_tokens; /* 0: bias row 0 for all tokens; else row = t / this */
+  int32_t gate_mode;         /* prism_gate_mode: what the k gate values of a token are */
 } prism_layer_desc;
 
 /*

@@ -97,12 +97,16 @@ class RouteResult:
 
 
 def route(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray], k: int,
-          bias_group_tokens: int = 0, token_pos: Optional[np.ndarray] = None) -> RouteResult:
+          bias_group_tokens: int = 0, token_pos: Optional[np.ndarray] = None,
+          renormalize: bool = True) -> RouteResult:
     """Gating network of Sec. III-A plus the frequency statistic f_n^l(e) of Sec. III-B.
 
     x [T,H], w_router [E,H], bias [G,E] fp32 or None.  Token t uses bias row
     pos(t) // bias_group_tokens (row 0 when bias_group_tokens == 0), where
     pos(t) = token_pos[t] if given else t.
+    renormalize: gates are the softmax over the k picked logits (they sum to 1);
+    otherwise the picked entries of the softmax over all E logits (the two model
+    families of Sec. IV differ in this; the paper does not say).
     """
     x64 = np.asarray(x, dtype=np.float64)
     w64 = np.asarray(w_router, dtype=np.float64)
@@ -126,7 +130,11 @@ def route(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray], k: in
         picked[tt, e] = True
     sel = logits[tt[:, None], idx].astype(np.float64)  # [T,k], slot 0 is the maximum
     w = np.exp(sel - sel[:, :1])
-    gate = (w / w.sum(axis=1, keepdims=True)).astype(np.float32)
+    if renormalize:
+        denom = w.sum(axis=1, keepdims=True)
+    else:
+        denom = np.exp(logits.astype(np.float64) - sel[:, :1]).sum(axis=1, keepdims=True)
+    gate = (w / denom).astype(np.float32)
     counts = np.zeros(E, dtype=np.int32)
     for t in range(T):
         for j in range(k):
@@ -275,12 +283,13 @@ class LayerResult:
 
 def moe_layer(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray], experts,
               shared: Sequence, mask: np.ndarray, k: int, dtype: str,
-              bias_group_tokens: int = 0, token_pos: Optional[np.ndarray] = None) -> LayerResult:
+              bias_group_tokens: int = 0, token_pos: Optional[np.ndarray] = None,
+              renormalize: bool = True) -> LayerResult:
     """One server's MoE layer forward: route -> dispatch -> local FFN -> combine."""
     x = np.asarray(x)
     T, H = x.shape
     es = 4 if dtype == "f32" else 2
-    r = route(x, w_router, bias, k, bias_group_tokens, token_pos)
+    r = route(x, w_router, bias, k, bias_group_tokens, token_pos, renormalize)
     d = dispatch(r.topk_idx, mask, H, es)
     y = expert_ffn(x, experts, shared, d.local_src, d.local_offsets, k)
     out = combine(y, d.local_src, r.topk_gate, T, len(shared), dtype)

@@ -22,6 +22,7 @@ SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism
            "prism_ceiling_mfma_bf16", "prism_ceiling_hbm_read", "prism_pack_remote",
            "prism_combine_remote")
 STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
+GATE_MODES = {"renormalized": 0, "softmax_all": 1}
 
 
 class PrismError(RuntimeError):
@@ -31,7 +32,7 @@ class PrismError(RuntimeError):
 class LayerDesc(ctypes.Structure):
     _fields_ = [("hidden", ctypes.c_int32), ("ffn", ctypes.c_int32), ("n_experts", ctypes.c_int32),
                 ("top_k", ctypes.c_int32), ("n_shared", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("bias_group_tokens", ctypes.c_int32)]
+                ("bias_group_tokens", ctypes.c_int32), ("gate_mode", ctypes.c_int32)]
 
 
 class ExpertWeights(ctypes.Structure):
@@ -101,9 +102,11 @@ def _stream(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
 
 
 def make_desc(hidden: int, ffn: int, n_experts: int, top_k: int, n_shared: int = 0,
-              dtype: str = "bf16", bias_group_tokens: int = 0) -> LayerDesc:
+              dtype: str = "bf16", bias_group_tokens: int = 0,
+              gate_mode: str = "renormalized") -> LayerDesc:
     return LayerDesc(hidden, ffn, n_experts, top_k, n_shared,
-                     PRISM_F32 if dtype == "f32" else PRISM_BF16, bias_group_tokens)
+                     PRISM_F32 if dtype == "f32" else PRISM_BF16, bias_group_tokens,
+                     GATE_MODES[gate_mode])
 
 
 def torch_dtype(desc: LayerDesc) -> torch.dtype:

@@ -9,6 +9,8 @@ prism_status validate_desc(const prism_layer_desc* d, int32_t T, bool need_ffn_s
   PRISM_RETURN_IF(d->hidden < 1 || d->n_experts < 1 || d->n_shared < 0, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(d->top_k < 1 || d->top_k > d->n_experts, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(d->bias_group_tokens < 0, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(d->gate_mode != PRISM_GATES_RENORMALIZED && d->gate_mode != PRISM_GATES_SOFTMAX_ALL,
+                  PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(d->dtype != PRISM_F32 && d->dtype != PRISM_BF16, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(d->n_experts > PRISM_MAX_EXPERTS || d->top_k > PRISM_MAX_TOPK ||
                       d->n_shared > PRISM_MAX_SHARED,

@@ -51,9 +51,9 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&v)[8]) {
 template <int NT>
 __device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0,
                                             const float* __restrict__ bias, int T, int E, int k,
-                                            int bias_group_tokens, float* __restrict__ logits,
-                                            int32_t* topk_idx, float* __restrict__ topk_gate,
-                                            int* s_counts) {
+                                            int bias_group_tokens, int gate_mode,
+                                            float* __restrict__ logits, int32_t* topk_idx,
+                                            float* __restrict__ topk_gate, int* s_counts) {
   const int lane = threadIdx.x & 63;
   const int r = lane & 15;
   const int q = lane >> 4;
@@ -111,9 +111,15 @@ __device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0,
       if (j == 0) sel0 = best;
       if (r == j) { mysel = best; myidx = bidx; }
     }
-    // gates: softmax over the k picked logits; lane r < k owns slot r
+    // gates: softmax over the k picked logits, or the picked entries of the softmax over
+    // all experts; lane r < k owns slot r, sel0 is the token's largest logit
     double w = r < k ? exp((double)mysel - (double)sel0) : 0.0;
     double sum = w;
+    if (gate_mode == PRISM_GATES_SOFTMAX_ALL) {
+      sum = 0.0;
+#pragma unroll
+      for (int n = 0; n < NT; ++n) sum += exp((double)lg[n][v] - (double)sel0);   // exp(-inf) = 0 past E
+    }
 #pragma unroll
     for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
     if (r < k && t < T) {
@@ -130,7 +136,7 @@ __device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0,
 template <typename TIn, int NT, bool PARTIAL>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
     const TIn* __restrict__ x, const TIn* __restrict__ w_router, const float* __restrict__ bias,
-    int T, int H, int E, int k, int bias_group_tokens, float* __restrict__ logits,
+    int T, int H, int E, int k, int bias_group_tokens, int gate_mode, float* __restrict__ logits,
     int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate, int32_t* __restrict__ counts,
     unsigned long long* __restrict__ counts_accum, int h_span, double* __restrict__ partial) {
   constexpr int EP = NT * 16;             // padded expert count
@@ -220,8 +226,8 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
     return;
   }
 
-  finish_tile<NT>(acc, tok0, bias, T, E, k, bias_group_tokens, logits, topk_idx, topk_gate,
-                  counts != nullptr ? s_counts : nullptr);
+  finish_tile<NT>(acc, tok0, bias, T, E, k, bias_group_tokens, gate_mode, logits, topk_idx,
+                  topk_gate, counts != nullptr ? s_counts : nullptr);
   if (counts == nullptr) return;   // the caller derives the counts from the dispatch histogram
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // this wavefront's LDS atomics, then its reads
 
@@ -249,7 +255,8 @@ constexpr int kFrontThreads = dispatch_dev::kThreads;
 template <int NT>
 __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
     double* partial, int n_hsplit, const float* __restrict__ bias, int T, int E,
-    int k, int S, int bias_group_tokens, int32_t* topk_idx, float* __restrict__ topk_gate,
+    int k, int S, int bias_group_tokens, int gate_mode, int32_t* topk_idx,
+    float* __restrict__ topk_gate,
     const uint8_t* __restrict__ mask, const dispatch_dev::SplitOut o,
     int32_t* __restrict__ local_src, int32_t* __restrict__ remote_src, int32_t* __restrict__ inv,
     const gg::SchedParams p0, const gg::SchedParams p1) {
@@ -281,8 +288,8 @@ __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
     for (int n = 0; n < NT; ++n)
       acc[n] = *reinterpret_cast<const f64x4*>(partial + (size_t)tile * n_hsplit * (NT * 256) +
                                                n * 256 + lane * 4);
-    finish_tile<NT>(acc, tile * kTokPerBlock, bias, T, E, k, bias_group_tokens, nullptr, topk_idx,
-                    topk_gate, nullptr);
+    finish_tile<NT>(acc, tile * kTokPerBlock, bias, T, E, k, bias_group_tokens, gate_mode, nullptr,
+                    topk_idx, topk_gate, nullptr);
   }
   __syncthreads();   // topk_idx is complete and visible to the whole workgroup
   dispatch_dev::dispatch_scatter_block<true>(topk_idx, T * k, E, mask, nullptr, 0, o, local_src,
@@ -318,7 +325,8 @@ prism_status launch_typed(const prism_layer_desc& d, const void* x, const void* 
 #define PRISM_ROUTE_LAUNCH(NT, PARTIAL)                                                          \
   hipLaunchKernelGGL((route_kernel<TIn, NT, PARTIAL>), grid, block,                              \
                      (size_t)(kWavesPerBlock / 2) * NT * 4 * 64 * 8, st, (const TIn*)x, (const TIn*)w,  \
-                     bias, T, d.hidden, E, d.top_k, d.bias_group_tokens, logits, idx, gate,     \
+                     bias, T, d.hidden, E, d.top_k, d.bias_group_tokens, d.gate_mode, logits,    \
+                     idx, gate,                                                                  \
                      counts, (unsigned long long*)accum, h_span, partial)
 #define PRISM_ROUTE_CASE(NT)                                                                     \
   do {                                                                                           \
@@ -389,7 +397,8 @@ prism_status launch_decode_front_end(const prism_layer_desc& d, const void* x, c
 #define PRISM_FRONT_CASE(NT)                                                                     \
   hipLaunchKernelGGL((decode_front_end_kernel<NT>), dim3(1), dim3(kFrontThreads), 0, st,        \
                      route_part, n_hsplit, bias, T, E, d.top_k, d.n_shared,                     \
-                     d.bias_group_tokens, topk_idx, topk_gate, mask, o, local_src, remote_src,  \
+                     d.bias_group_tokens, d.gate_mode, topk_idx, topk_gate, mask, o, local_src,  \
+                     remote_src,                                                                 \
                      inv, p0, p1)
   const int nt = route_col_tiles(E);
   if (nt <= 1) PRISM_FRONT_CASE(1);

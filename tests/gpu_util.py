@@ -17,8 +17,8 @@ def to_f32(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy()
 
 
-def desc_of(cfg):
-    return P.make_desc(cfg.H, cfg.F, cfg.E, cfg.k, cfg.S, cfg.dtype, cfg.bias_group_tokens)
+def desc_of(cfg, gate_mode="renormalized"):
+    return P.make_desc(cfg.H, cfg.F, cfg.E, cfg.k, cfg.S, cfg.dtype, cfg.bias_group_tokens, gate_mode)
 
 
 def weight_table(inp, mask=None, all_experts=False):
@@ -35,14 +35,14 @@ def weight_table(inp, mask=None, all_experts=False):
     return P.WeightTable(experts, shared)
 
 
-def oracle_layer(inp, mask=None, x=None, token_pos=None):
+def oracle_layer(inp, mask=None, x=None, token_pos=None, renormalize=True):
     c = inp.cfg
     f = inp.f32
     return O.moe_layer(f(inp.x) if x is None else x, f(inp.w_router), inp.bias,
                        lambda e: tuple(f(w) for w in inp.expert(e)),
                        [tuple(f(w) for w in inp.shared(s)) for s in range(c.S)],
                        inp.mask if mask is None else mask, c.k, c.dtype, c.bias_group_tokens,
-                       token_pos)
+                       token_pos, renormalize)
 
 
 def rel_err(a, ref):
@@ -58,8 +58,8 @@ def rel_err(a, ref):
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
-def run_layer(cfg, inp, mask=None, wt=None, ws=None, **kw):
-    desc = desc_of(cfg)
+def run_layer(cfg, inp, mask=None, wt=None, ws=None, gate_mode="renormalized", **kw):
+    desc = desc_of(cfg, gate_mode)
     ws = P.alloc_workspace(desc, cfg.T) if ws is None else ws
     mask = inp.mask if mask is None else mask
     wt = weight_table(inp, mask) if wt is None else wt

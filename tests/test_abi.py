@@ -71,6 +71,15 @@ def test_validation_error_codes(kw, status):
     assert P.load_library().prism_workspace_bytes(ctypes.byref(d), 16, ctypes.byref(n)) == status
 
 
+def test_unknown_gate_mode_is_rejected():
+    d = P.make_desc(128, 128, 8, 2, 0, "bf16")
+    d.gate_mode = 7
+    n = ctypes.c_size_t(0)
+    assert P.load_library().prism_workspace_bytes(ctypes.byref(d), 16, ctypes.byref(n)) == 1
+    d.gate_mode = 1
+    assert P.load_library().prism_workspace_bytes(ctypes.byref(d), 16, ctypes.byref(n)) == 0
+
+
 def test_null_pointers_and_negative_tokens_are_rejected_before_any_launch():
     lib = P.load_library()
     d = P.make_desc(128, 128, 8, 2, 0, "bf16")

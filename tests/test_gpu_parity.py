@@ -204,6 +204,23 @@ def test_moe_layer_parity(case):
     print(f"{case}: layer out err {err:.3g}")
 
 
+@pytest.mark.parametrize("case", ["mixtral_small", "finegrained_small", "dsv2_decode", "tiny_f32",
+                                  "decode_one_token"])
+def test_unrenormalised_gates_parity(case):
+    """Gate convention of the other model family: picked entries of the softmax over all experts."""
+    cfg, inp = _inputs(case)
+    ref = oracle_layer(inp, renormalize=False)
+    assert np.all(ref.route.topk_gate.astype(np.float64).sum(axis=1) < 1.0)
+    o = _run_layer(cfg, inp, gate_mode="softmax_all")
+    err = _check_layer(cfg, o, ref)
+    got = P.prism_route(desc_of(cfg, "softmax_all"), to_dev(inp.x), to_dev(inp.w_router),
+                        to_dev(inp.bias))
+    torch.cuda.synchronize()
+    assert np.array_equal(got.topk_idx.cpu().numpy(), ref.route.topk_idx)
+    assert np.max(np.abs(got.topk_gate.cpu().numpy() - ref.route.topk_gate)) <= 1e-6
+    print(f"{case}: layer out err {err:.3g}")
+
+
 def test_moe_layer_second_phase_mask_change():
     cfg, p0 = _inputs("dsv2_small", 0)
     _, p1 = _inputs("dsv2_small", 1)

@@ -435,3 +435,31 @@ def test_remote_call_completes_the_layer():
     # nothing remote: nothing added
     same = O.combine_remote(full.out, np.zeros((0, H)), np.zeros(0, np.int64), full.route.topk_gate, "f32")
     assert np.array_equal(same, full.out)
+
+
+# ---------------------------------------------------------------------------
+# gates without renormalisation: the picked entries of the softmax over all experts
+# ---------------------------------------------------------------------------
+
+def test_unrenormalised_gates():
+    rng = np.random.default_rng(31)
+    T, H, E, k = 40, 24, 10, 3
+    x = rng.standard_normal((T, H)).astype(np.float32)
+    w = rng.standard_normal((E, H)).astype(np.float32)
+    b = rng.standard_normal((1, E)).astype(np.float32)
+    a = O.route(x, w, b, k)
+    u = O.route(x, w, b, k, renormalize=False)
+    assert np.array_equal(a.topk_idx, u.topk_idx) and np.array_equal(a.counts, u.counts)
+    # library value: torch softmax over all experts, gathered at the picks
+    p = torch.softmax(torch.from_numpy(u.logits.astype(np.float64)), dim=1).numpy()
+    assert np.max(np.abs(u.topk_gate - np.take_along_axis(p, u.topk_idx.astype(np.int64), 1))) <= 1e-7
+    s = u.topk_gate.astype(np.float64).sum(axis=1)
+    assert np.all(s < 1.0) and np.all(s > 0.0)                       # mass of the other experts is left out
+    # dividing by their sum gives back the renormalised gates
+    assert np.max(np.abs(u.topk_gate / s[:, None] - a.topk_gate)) <= 1e-6
+    # k = E: nothing is left out, both conventions coincide
+    full_a, full_u = O.route(x, w, b, E), O.route(x, w, b, E, renormalize=False)
+    assert np.max(np.abs(full_a.topk_gate - full_u.topk_gate)) <= 1e-7
+    # zero router, no bias: every expert has probability 1/E
+    z = O.route(x, np.zeros_like(w), None, k, renormalize=False)
+    assert np.allclose(z.topk_gate, 1.0 / E, rtol=0, atol=1e-7)
