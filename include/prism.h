@@ -17,7 +17,9 @@
  *                 the fp32 bias is added in fp32)
  *   top-k      : k picks per token by descending logit, lowest expert index
  *                wins ties; slot j holds the j-th pick
- *   gate[t,j]  = exp(l_j - l_0) / sum_j' exp(l_j' - l_0)   (sums to 1)
+ *   gate[t,j]  = exp(l_j - l_0) / sum_j' exp(l_j' - l_0)   (sums to 1; with
+ *                gate_mode PRISM_GATES_SOFTMAX_ALL the sum in the denominator
+ *                runs over all E experts instead of the k picks)
  *   counts[e]  = number of (t,j) with topk_idx[t,j] == e   (all experts,
  *                hosted or not: the raw f_n^l(e))
  *   local(a)   = local_mask[topk_idx[a]] != 0 for assignment a = t*k + j
