@@ -1,0 +1,50 @@
+"""bench.py's contract with the driver: one JSON line with the agreed keys, and a refusal of
+more than one GPU (this build has no sharded path)."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BENCH = os.path.join(ROOT, "bench.py")
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = subprocess.run([sys.executable, BENCH, "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="4")
+    r = subprocess.run([sys.executable, BENCH], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("config,bound,unit", [("cfg3_mixtral_decode", "hbm", "GB/s"),
+                                               ("cfg4_finegrained", "mfma", "TFLOP/s")])
+def test_bench_prints_one_json_line_with_the_contract_keys(config, bound, unit):
+    r = subprocess.run([sys.executable, BENCH, "--config", config, "--steps", "3", "--warmup", "1",
+                        "--cpu-sample-tokens", "8"], capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step",
+                "higher_is_better", "scaling", "vs_baseline", "dtype", "data", "config", "roofline",
+                "cpu_baseline"):
+        assert key in d, key
+    assert d["metric"] == "moe_layer_tokens_per_sec" and d["unit"] == "tokens/s"
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["warmup"] == 1
+    assert d["higher_is_better"] is True and d["vs_baseline"] is None and d["data"] == "synthetic"
+    assert d["config"]["workload"] == config and "model" not in d["config"]
+    assert d["value"] == pytest.approx(d["config"]["tokens"] / (d["ms_per_step"] * 1e-3), rel=1e-6)
+    rf = d["roofline"]
+    assert rf["bound"] == bound and rf["unit"] == unit
+    assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"], rel=1e-9)
+    assert 0 < rf["frac"] < 1 and rf["kernel_ms"] > 0
+    cb = d["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["unit"] == "tokens/s" and cb["value"] > 0 and cb["cores"] >= 1
+    assert "sample" in cb and "8" in cb["sample"]
+    assert set(d["measured_ceilings"]) == {"mfma_bf16_constant_operands_tflops",
+                                           "mfma_bf16_random_operands_tflops", "hbm_read_gbs"}
