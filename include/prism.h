@@ -118,8 +118,11 @@ const char* prism_status_string(prism_status s);
 /*
  * Workspace size in bytes (written to the host variable *bytes) that any
  * entry point below needs for a batch of up to max_tokens tokens of this
- * layer.  The workspace must be 256-byte aligned; its contents between calls
- * are irrelevant.
+ * layer.  The size never shrinks as max_tokens grows, so a workspace sized for
+ * the largest batch serves every smaller one.  The workspace must be 256-byte
+ * aligned; its contents between calls are irrelevant; two calls that use the
+ * same workspace must not overlap in time (run them on one stream, or give
+ * each stream its own workspace).
  */
 prism_status prism_workspace_bytes(const prism_layer_desc* desc, int32_t max_tokens, size_t* bytes);
 
