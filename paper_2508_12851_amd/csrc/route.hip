@@ -48,8 +48,10 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&v)[8]) {
 // From the complete fp64 logit tile of 16 tokens (held by one wavefront in the
 // accumulator layout of v_mfma_f64_16x16x4) to top-k indices and gates.  Run by one
 // whole wavefront.  s_counts (LDS, may be NULL) receives +1 per selected expert.
+// v_mask (wave-uniform): bit v set = handle the four tokens 4v + q of the tile, so
+// several wavefronts can share one tile's work.
 template <int NT>
-__device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0,
+__device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0, int v_mask,
                                             const float* __restrict__ bias, int T, int E, int k,
                                             int bias_group_tokens, int gate_mode,
                                             float* __restrict__ logits, int32_t* topk_idx,
@@ -66,6 +68,7 @@ __device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0,
     const int e = n * 16 + r;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
+      if (!((v_mask >> v) & 1)) continue;
       const int t = tok0 + 4 * v + q;
       float val = (float)acc[n][v];
       if (e < E && t < T) {
@@ -86,6 +89,7 @@ __device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0,
   // group; equal logits resolve to the lower expert index.
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
+    if (!((v_mask >> v) & 1)) continue;
     const int t = tok0 + 4 * v + q;
     float vals[NT];
 #pragma unroll
@@ -226,7 +230,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
     return;
   }
 
-  finish_tile<NT>(acc, tok0, bias, T, E, k, bias_group_tokens, gate_mode, logits, topk_idx,
+  finish_tile<NT>(acc, tok0, 0xF, bias, T, E, k, bias_group_tokens, gate_mode, logits, topk_idx,
                   topk_gate, counts != nullptr ? s_counts : nullptr);
   if (counts == nullptr) return;   // the caller derives the counts from the dispatch histogram
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");   // this wavefront's LDS atomics, then its reads
@@ -282,14 +286,19 @@ __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
     *reinterpret_cast<f64x4*>(base) = sum;
   }
   __syncthreads();   // the sums are visible to the whole workgroup
-  for (int tile = wave; tile < n_tiles; tile += kFrontThreads / kWave) {
+  // A tile's routing is four units of four tokens (accumulator register v holds tokens
+  // 4v + q); wavefront w takes unit v = w of every tile, so even a 16-token batch keeps all
+  // four wavefronts busy.
+  static_assert(kFrontThreads / kWave == 4, "one wavefront per accumulator register index");
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    const int v_mask = 1 << wave;
     f64x4 acc[NT];
 #pragma unroll
     for (int n = 0; n < NT; ++n)
       acc[n] = *reinterpret_cast<const f64x4*>(partial + (size_t)tile * n_hsplit * (NT * 256) +
                                                n * 256 + lane * 4);
-    finish_tile<NT>(acc, tile * kTokPerBlock, bias, T, E, k, bias_group_tokens, gate_mode, nullptr,
-                    topk_idx, topk_gate, nullptr);
+    finish_tile<NT>(acc, tile * kTokPerBlock, v_mask, bias, T, E, k, bias_group_tokens, gate_mode,
+                    nullptr, topk_idx, topk_gate, nullptr);
   }
   __syncthreads();   // topk_idx is complete and visible to the whole workgroup
   dispatch_dev::dispatch_scatter_block<true>(topk_idx, T * k, E, mask, nullptr, 0, o, local_src,
