@@ -29,7 +29,7 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // ---------------------------------------------------------------------------
 constexpr int kDispatchChunk = 2048;   // assignments per dispatch block
 constexpr int kDecodeMaxTokens = 64;    // batches up to this size take the weight-streaming path
-constexpr int kDecodeSplits = 8;        // contraction slices of its down projection
+constexpr int kDecodeSplits = 4;        // contraction slices of its down projection (4 beat 8 and 2 when timed)
 constexpr int kMinTileM = 64;           // smallest row tile of the grouped GEMM (bounds table sizes)
 constexpr int kRouteTokTile = 16;       // tokens per router tile
 constexpr int kRouteMaxHSplit = 16;     // hidden-dimension slices of the decode router
