@@ -262,6 +262,19 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                                     void* stream, void* const* stage_events);
 
 /*
+ * Debug helper, NOT asynchronous: copies the pointer tables and the mask back
+ * to the host (blocking copies on the default stream) and checks what the fast
+ * path assumes without checking: every hosted expert (local_mask[e] != 0) and
+ * every shared expert has three non-NULL, 16-byte aligned weight pointers.
+ * Returns PRISM_OK, or PRISM_ERR_INVALID_ARG with *bad_expert (host, may be
+ * NULL) set to the first offending routed expert, or to E + s for shared
+ * expert s.  PRISM_ERR_LAUNCH if a copy fails.
+ */
+prism_status prism_debug_check_weights(const prism_layer_desc* desc,
+                                       const prism_expert_weights* weights,
+                                       const uint8_t* local_mask, int32_t* bad_expert);
+
+/*
  * Measured ceilings for measurement harnesses (not steps of the method).  Both
  * calls only enqueue one kernel on `stream`; the caller times it.
  *

@@ -20,7 +20,7 @@ PRISM_F32, PRISM_BF16 = 0, 1
 SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism_dispatch",
            "prism_expert_ffn", "prism_combine", "prism_moe_layer", "prism_moe_layer_traced",
            "prism_ceiling_mfma_bf16", "prism_ceiling_hbm_read", "prism_pack_remote",
-           "prism_combine_remote")
+           "prism_combine_remote", "prism_debug_check_weights")
 STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
 GATE_MODES = {"renormalized": 0, "softmax_all": 1}
 
@@ -70,6 +70,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.prism_moe_layer_traced.argtypes = lib.prism_moe_layer.argtypes + [vp]
     lib.prism_pack_remote.argtypes = [dp, vp, vp, vp, i32, vp, vp]
     lib.prism_combine_remote.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.prism_debug_check_weights.argtypes = [dp, wp, vp, ctypes.POINTER(i32)]
     lib.prism_ceiling_mfma_bf16.argtypes = [vp, vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.prism_ceiling_hbm_read.argtypes = [vp, sz, vp, i32, vp]
     for name in SYMBOLS:
@@ -306,3 +307,13 @@ def prism_combine_remote(desc: LayerDesc, y_remote, remote_src, remote_offsets, 
                                                _ptr(workspace), workspace.numel(), _stream(stream)),
            "prism_combine_remote")
     return out
+
+
+def prism_debug_check_weights(desc: LayerDesc, weights: WeightTable, local_mask) -> None:
+    """Blocking check that every hosted and every shared expert has usable weight pointers."""
+    bad = ctypes.c_int32(-1)
+    code = load_library().prism_debug_check_weights(ctypes.byref(desc), ctypes.byref(weights.struct),
+                                                    _ptr(local_mask), ctypes.byref(bad))
+    if code != 0:
+        what = f"expert {bad.value}" if bad.value >= 0 else "arguments"
+        _check(code, f"prism_debug_check_weights ({what})")

@@ -156,6 +156,38 @@ prism_status prism_combine_remote(const prism_layer_desc* desc, const void* y_re
   return launch_combine(*desc, y_remote, ws.inv, topk_gate, T, out, st, nullptr, 0, true);
 }
 
+prism_status prism_debug_check_weights(const prism_layer_desc* desc,
+                                       const prism_expert_weights* weights,
+                                       const uint8_t* local_mask, int32_t* bad_expert) {
+  PRISM_TRY(validate_desc(desc, 0, false));
+  PRISM_TRY(check_weights(*desc, weights));
+  PRISM_RETURN_IF(local_mask == nullptr, PRISM_ERR_INVALID_ARG);
+  const int E = desc->n_experts, S = desc->n_shared;
+  uint8_t mask[PRISM_MAX_EXPERTS];
+  const void* routed[3][PRISM_MAX_EXPERTS];
+  const void* shared[3][PRISM_MAX_SHARED];
+  const void* const* rt[3] = {weights->w_gate, weights->w_up, weights->w_down};
+  const void* const* sh[3] = {weights->shared_w_gate, weights->shared_w_up, weights->shared_w_down};
+  if (hipMemcpy(mask, local_mask, (size_t)E, hipMemcpyDeviceToHost) != hipSuccess) return PRISM_ERR_LAUNCH;
+  for (int i = 0; i < 3; ++i) {
+    if (hipMemcpy(routed[i], rt[i], (size_t)E * sizeof(void*), hipMemcpyDeviceToHost) != hipSuccess)
+      return PRISM_ERR_LAUNCH;
+    if (S > 0 && hipMemcpy(shared[i], sh[i], (size_t)S * sizeof(void*), hipMemcpyDeviceToHost) != hipSuccess)
+      return PRISM_ERR_LAUNCH;
+  }
+  auto bad = [](const void* p) { return p == nullptr || ((uintptr_t)p & 15u) != 0; };
+  for (int e = 0; e < E + S; ++e) {
+    const bool hosted = e >= E || mask[e] != 0;
+    if (!hosted) continue;
+    for (int i = 0; i < 3; ++i)
+      if (bad(e < E ? routed[i][e] : shared[i][e - E])) {
+        if (bad_expert != nullptr) *bad_expert = e;
+        return PRISM_ERR_INVALID_ARG;
+      }
+  }
+  return PRISM_OK;
+}
+
 prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                                     const void* w_router, const float* router_bias,
                                     const prism_expert_weights* weights,

@@ -99,3 +99,17 @@ def test_unsupported_shapes_and_small_workspaces_are_refused_before_any_launch()
         P.prism_moe_layer(d, torch.zeros((4096, 128), **bf), torch.zeros((8, 128), **bf), None,
                           P.WeightTable(hosted, []), torch.ones(8, dtype=torch.uint8, device="cuda"),
                           small)
+
+
+def test_debug_check_finds_a_hosted_expert_without_weights():
+    cfg = make_config("cfg4_finegrained", T=16, H=128, F=192, bias_group_tokens=0)
+    inp = make_inputs(cfg)
+    desc = desc_of(cfg)
+    mask = to_dev(inp.mask)
+    P.prism_debug_check_weights(desc, weight_table(inp), mask)            # hosted ones are all there
+    hosted = int(np.flatnonzero(inp.mask)[3])
+    holes = inp.mask.copy()
+    holes[hosted] = 0                                                     # table without that expert ...
+    with pytest.raises(P.PrismError, match=f"expert {hosted}"):
+        P.prism_debug_check_weights(desc, weight_table(inp, holes), mask)  # ... but the mask hosts it
+    P.prism_debug_check_weights(desc, weight_table(inp, holes), to_dev(holes))
