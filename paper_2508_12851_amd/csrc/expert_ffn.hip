@@ -161,7 +161,7 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   const int nt1 = ceil_div(d.ffn, C1::BN / 2);     // GEMM1 tile: BN/2 gate rows + BN/2 up rows
   const int nt2 = ceil_div(d.hidden, C2::BN);
   if (!schedules_built)
-    PRISM_TRY(gg::launch_build_schedules(d, local_offsets, T, C1::BM, nt1, sched1, C2::BM, nt2, sched2, st));
+    PRISM_TRY(gg::launch_build_schedules(d, local_offsets, T, C1::BM, nt1, sched1, C2::BM, nt2, sched2, kRotate, st));
 
   GemmArgs g1{};
   g1.A = (const uint16_t*)x;

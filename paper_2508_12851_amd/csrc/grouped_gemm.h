@@ -27,11 +27,10 @@
 // land while the epilogue of the first stores its results.
 //
 // Work order: the hardware hands consecutive workgroup ids to the 8 XCDs in
-// turn, each with a private L2.  Every (expert, column tile) pair is owned by
-// one XCD (pairs are dealt round-robin, so the XCDs stay balanced), and an
-// XCD's list walks its pairs with the row tiles fastest: the workgroups
-// resident on one XCD share a few weight tiles and one expert's activation
-// tiles, and every weight tile is fetched into exactly one L2.
+// turn, each with a private L2.  The schedule (schedule.h) gives every XCD one
+// list of items in which consecutive items form small rectangles of row tiles x
+// column tiles of one expert, so the workgroups resident on an XCD share a few
+// activation tiles and a few weight tiles in that XCD's L2.
 #ifndef PRISM_GROUPED_GEMM_H_
 #define PRISM_GROUPED_GEMM_H_
 
@@ -462,13 +461,14 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
 }
 
 // Launches the schedule builder for the two GEMMs of the FFN: row tiles bm1 / bm2,
-// nt1 / nt2 column tiles.
+// nt1 / nt2 column tiles; interleave as in SchedParams.
 static inline prism_status launch_build_schedules(const prism_layer_desc& d,
                                                   const int32_t* local_offsets, int T, int bm1,
                                                   int nt1, int32_t* sched1, int bm2, int nt2,
-                                                  int32_t* sched2, hipStream_t st) {
-  const SchedParams p0{bm1, nt1, sched_capacity(d, T, bm1, nt1), sched1};
-  const SchedParams p1{bm2, nt2, sched_capacity(d, T, bm2, nt2), sched2};
+                                                  int32_t* sched2, bool interleave,
+                                                  hipStream_t st) {
+  const SchedParams p0{bm1, nt1, sched_capacity(d, T, bm1, nt1), sched1, interleave ? 1 : 0};
+  const SchedParams p1{bm2, nt2, sched_capacity(d, T, bm2, nt2), sched2, interleave ? 1 : 0};
   hipLaunchKernelGGL(build_schedule_kernel, dim3(2), dim3(512), 0, st, local_offsets, d.n_experts,
                      d.n_shared, T, T * d.top_k, p0, p1);
   PRISM_CHECK_LAUNCH();

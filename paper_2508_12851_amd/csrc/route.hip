@@ -399,9 +399,9 @@ prism_status launch_decode_front_end(const prism_layer_desc& d, const void* x, c
                                  (unsigned long long*)counts_accum, d.hidden * elem_size(d.dtype)};
   int bm1, nt1, bm2, nt2;
   decode_schedule_shapes(d, &bm1, &nt1, &bm2, &nt2);
-  const gg::SchedParams p0{bm1, nt1, gg::sched_capacity(d, T, bm1, nt1), tiles};
+  const gg::SchedParams p0{bm1, nt1, gg::sched_capacity(d, T, bm1, nt1), tiles, 1};
   const gg::SchedParams p1{bm2, nt2, gg::sched_capacity(d, T, bm2, nt2),
-                           tiles + tile_table_ints(d, T)};
+                           tiles + tile_table_ints(d, T), 1};
   trace(stage_events, PRISM_STAGE_DISPATCH, 0, st);
 #define PRISM_FRONT_CASE(NT)                                                                     \
   hipLaunchKernelGGL((decode_front_end_kernel<NT>), dim3(1), dim3(kFrontThreads), 0, st,        \

@@ -21,12 +21,46 @@ constexpr int kItemInts = 8;         // ints per work item
 //     [2] rows in the tile (1..BM)
 //     [3] first token of the tile for shared experts, -1 for routed ones
 //     [4] column tile
+//
+// Work order.  The (row tile, column tile) grid of every group is cut into rectangles of
+// about kRectRows x kRectCols tiles (a group's row tiles and the column tiles are split
+// into equal parts no larger than that).  All items, rectangle after rectangle (groups in
+// order, row parts, then column parts; inside a rectangle the row tiles run fastest), form
+// one sequence, and XCD x gets the x-th eighth of it.  So the 32 workgroups resident on an
+// XCD work at any time on one or two rectangles -- about 8 activation tiles and 4 weight
+// tiles for 32 items instead of one of each per item -- which is what the XCD's L2 can
+// share among them, and the eight lists have the same length to within one item.
+// The number of items (row tiles x column tiles) must stay below 2^31, which the int
+// capacity of a list already implies.
+constexpr int kRectRows = 8;
+constexpr int kRectCols = 4;
+
 struct SchedParams {
   int BM;            // row tile
   int n_ntiles;      // column tiles
   int capacity;      // items one XCD list can hold
   int32_t* sched;
+  int interleave;    // 1: deal the sequence to the XCDs item by item instead of in eighths
+                     // (schedules whose items share nothing: every XCD then reads from all
+                     // parts of the weight matrices at any time)
 };
+
+// Equal split of `count` things into the fewest parts of at most `part_max`: which part
+// holds element i, where that part starts and how long it is.
+struct PartOf {
+  int first, len;
+};
+__device__ __forceinline__ PartOf part_of(int i, int count, int part_max) {
+  const int parts = (count + part_max - 1) / part_max;
+  const int base = count / parts, extra = count % parts;     // `extra` parts have base + 1
+  const int split = extra * (base + 1);
+  if (i < split) {
+    const int q = i / (base + 1);
+    return PartOf{q * (base + 1), base + 1};
+  }
+  const int q = (i - split) / base;
+  return PartOf{split + q * base, base};
+}
 
 // Builds NS (1 or 2) schedules of the same row groups side by side; called by every
 // thread of a workgroup (any size that is a multiple of 64).  Inside, only LDS data
@@ -39,8 +73,6 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
                                                       const SchedParams (&p)[NS]) {
   __shared__ int s_rows[kMaxGroups], s_row0[kMaxGroups];
   __shared__ int s_start[NS][kMaxGroups + 1];            // first row tile of group g
-  __shared__ int s_rank[NS][kMaxGroups];                 // index of g among the non-empty groups
-  __shared__ int s_base[NS][kXcds][kMaxGroups + 1];      // items of XCD x before group g
   const int G = E + S;
   // p[s] for a thread-dependent s, without indexing the parameter array at run time
   // (that would put it in scratch memory)
@@ -61,45 +93,30 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
   if (threadIdx.x < NS) {
     const int s = threadIdx.x;
     const SchedParams ps = pick(s);
-    const int BM = ps.BM;
-    int run = 0, rank = 0;
-    for (int g = 0; g < G; ++g) {
-      s_start[s][g] = run;
-      s_rank[s][g] = rank;
-      const int m = (s_rows[g] + BM - 1) / BM;
-      run += m;
-      rank += m > 0;
-    }
-    s_start[s][G] = run;
-    ps.sched[0] = run;
-    ps.sched[1] = ps.capacity;
-  }
-  lds_barrier();
-  // Pair (g, nt) has index q = rank(g) * n_ntiles + nt and belongs to XCD q % 8.
-  // XCD x owns the column tiles r, r + 8, ... of group g with r = (x - rank(g) n_ntiles) mod 8.
-  auto first_nt = [&](int s, int n_ntiles, int g, int x) {
-    const int r = (x - s_rank[s][g] * n_ntiles) % kXcds;
-    return r < 0 ? r + kXcds : r;
-  };
-  if (threadIdx.x < NS * kXcds) {
-    const int s = threadIdx.x / kXcds, x = threadIdx.x % kXcds;
-    const SchedParams ps = pick(s);
-    const int n_ntiles = ps.n_ntiles;
     int run = 0;
     for (int g = 0; g < G; ++g) {
-      s_base[s][x][g] = run;
-      const int m = s_start[s][g + 1] - s_start[s][g];
-      const int r = first_nt(s, n_ntiles, g, x);
-      const int c = r < n_ntiles ? (n_ntiles - 1 - r) / kXcds + 1 : 0;
-      run += m * c;
+      s_start[s][g] = run;
+      run += (s_rows[g] + ps.BM - 1) / ps.BM;
     }
-    s_base[s][x][G] = run;
-    ps.sched[4 + x] = run;
+    s_start[s][G] = run;
+    const unsigned total = (unsigned)run * (unsigned)ps.n_ntiles;
+    const unsigned per_xcd = (total + kXcds - 1) / kXcds;
+    ps.sched[0] = run;
+    ps.sched[1] = ps.capacity;
+    for (unsigned x = 0; x < (unsigned)kXcds; ++x) {
+      unsigned count;
+      if (ps.interleave)   // items x, x + 8, ...
+        count = total > x ? (total - x + kXcds - 1) / kXcds : 0;
+      else                 // every list holds per_xcd items, the last non-empty one the remainder
+        count = total > x * per_xcd ? min(per_xcd, total - x * per_xcd) : 0;
+      ps.sched[4 + x] = (int)count;
+    }
   }
   lds_barrier();
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
     const int BM = p[s].BM, n_ntiles = p[s].n_ntiles, capacity = p[s].capacity;
+    const bool interleave = p[s].interleave != 0;
     const int n_mtiles = s_start[s][G];
     auto group_of_tile = [&](int i) {   // largest g with s_start[g] <= i (skips empty groups)
       int lo = 0, hi = G;               // invariant: s_start[lo] <= i < s_start[hi]
@@ -109,14 +126,21 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
       }
       return lo;
     };
-    const long long n_items = (long long)n_mtiles * n_ntiles;
-    for (long long w = threadIdx.x; w < n_items; w += blockDim.x) {
-      const int i = (int)(w % n_mtiles), nt = (int)(w / n_mtiles);
+    const unsigned n_items = (unsigned)n_mtiles * (unsigned)n_ntiles;
+    const unsigned per_xcd = (n_items + kXcds - 1) / kXcds;
+    for (unsigned w = threadIdx.x; w < n_items; w += blockDim.x) {
+      const int i = (int)(w % (unsigned)n_mtiles), nt = (int)(w / (unsigned)n_mtiles);
       const int g = group_of_tile(i);
       const int mi = i - s_start[s][g];
       const int m = s_start[s][g + 1] - s_start[s][g];
-      const int x = (s_rank[s][g] * n_ntiles + nt) % kXcds;
-      const int pos = s_base[s][x][g] + ((nt - first_nt(s, n_ntiles, g, x)) / kXcds) * m + mi;   // row tiles fastest
+      const PartOf rp = part_of(mi, m, kRectRows);          // this item's rectangle: rows ...
+      const PartOf cp = part_of(nt, n_ntiles, kRectCols);   // ... and columns
+      // items before it: earlier groups, earlier row parts of its group, earlier rectangles of
+      // its row part, earlier columns of its rectangle, earlier rows of its column
+      const unsigned seq = (unsigned)(s_start[s][g] + rp.first) * (unsigned)n_ntiles +
+                           (unsigned)(rp.len * cp.first + (nt - cp.first) * rp.len + (mi - rp.first));
+      const unsigned x = interleave ? seq % kXcds : seq / per_xcd;
+      const unsigned pos = interleave ? seq / kXcds : seq - x * per_xcd;
       int4* out = reinterpret_cast<int4*>(p[s].sched + kSchedHeader +
                                           ((size_t)x * capacity + pos) * kItemInts);
       out[0] = int4{g, s_row0[g] + mi * BM, min(BM, s_rows[g] - mi * BM), g < E ? -1 : mi * BM};
