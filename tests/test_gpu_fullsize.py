@@ -109,3 +109,16 @@ def test_cfg5_migration_full_size_both_phases():
                               weight_table(p1, all_experts=True), to_dev(p0.mask), ws)
     torch.cuda.synchronize()
     assert int(stale.n_local_remote[0]) / cfg.A < ratios[1]
+
+
+def test_large_ragged_batch():
+    """Many more tokens than any benchmark config (79 dispatch chunks, ~800 row tiles, a
+    ragged last tile everywhere): integer outputs exhaustive, layer output on a sample."""
+    from prism_inputs import make_config
+    cfg = make_config("cfg4_finegrained", T=40001, H=512, F=640, E=32, k=4, S=1, n_local=19,
+                      bias_group_tokens=4096)
+    inp = make_inputs(cfg, weights="local", threads=16)
+    o = _run(cfg, inp)
+    _check_integers(cfg, inp, o)
+    err = _check_sampled_output(cfg, inp, o, 96, seed=11)
+    print(f"large batch: sampled out err {err:.3g}")
