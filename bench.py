@@ -229,7 +229,7 @@ def main():
         roofline["frac_of_measured_ceiling"] = roofline["achieved"] / ref
         log("[bench] measured ceilings: " + ", ".join(f"{k}={v:.1f}" for k, v in ceil.items()))
     if not args.no_cpu_baseline:
-        n_sample = args.cpu_sample_tokens or (cfg.T if decode else 2048)
+        n_sample = args.cpu_sample_tokens or cfg.T      # the whole batch: a few seconds of numpy
         result["cpu_baseline"] = cpu_baseline(inp, n_sample)
     print(json.dumps(result), flush=True)
 
