@@ -178,6 +178,17 @@ def main():
     ms_per_step = 1e3 * elapsed / steps
     tokens_per_s = cfg.T * steps / elapsed
 
+    # per-step times from separate, individually bracketed calls (outside the timed region)
+    n_ind = min(steps, 50)
+    ind = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(n_ind)]
+    for i, (e0, e1) in enumerate(ind):
+        e0.record()
+        step(i)
+        e1.record()
+    torch.cuda.synchronize()
+    step_ms = sorted(e0.elapsed_time(e1) for e0, e1 in ind)
+
     stage_ms = {}
     for s in traced:
         stage_ms[P.STAGES[s]] = float(np.mean([events[i][s][0].elapsed_time(events[i][s][1])
@@ -221,6 +232,7 @@ def main():
                    "weight_copies_rotated": len(tables)},
         "roofline": roofline,
         "layer_tflops": layer_flop / (ms_per_step * 1e-3) / 1e12,
+        "step_ms_median": step_ms[len(step_ms) // 2], "step_ms_min": step_ms[0],
     }
     if not args.no_ceilings:
         ceil = measured_ceilings(torch, P)
