@@ -486,12 +486,10 @@ prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int
   constexpr int kCusPerXcd = 32;
   constexpr int kResident = (160 * 1024) / smem;     // workgroups per CU that fit in LDS
   auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK, ROTATE>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-      return PRISM_ERR_LAUNCH;
-    attr_set = true;
-  }
+  // once per instantiation (thread-safe initialisation of a local static)
+  static const bool attr_ok =
+      hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem) == hipSuccess;
+  if (!attr_ok) return PRISM_ERR_LAUNCH;
   if (capacity <= 0) return PRISM_OK;
   const int splits = SPLITK ? n_splits : 1;
   int slots = kCusPerXcd * kResident / splits;       // persistent workgroups per XCD

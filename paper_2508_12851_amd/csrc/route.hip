@@ -321,16 +321,16 @@ prism_status launch_typed(const prism_layer_desc& d, const void* x, const void* 
   const int h_span = route_h_span(d.hidden);
   const dim3 grid(ceil_div(T, kTokPerBlock), partial != nullptr ? ceil_div(d.hidden, h_span) : 1);
   const dim3 block(kWavesPerBlock * kWave);
-  static bool attr_set = false;
-  if (!attr_set) {   // the 256-expert tile needs 128 KiB of LDS for the partial sums
+  // the 256-expert tile needs 128 KiB of LDS for the partial sums; raised once (thread-safe
+  // initialisation of a local static)
+  static const bool attr_ok = [] {
     const int bytes = (kWavesPerBlock / 2) * 16 * 4 * 64 * 8;
-    if (hipFuncSetAttribute((const void*)route_kernel<TIn, 16, false>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess ||
-        hipFuncSetAttribute((const void*)route_kernel<TIn, 16, true>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
-      return PRISM_ERR_LAUNCH;
-    attr_set = true;
-  }
+    return hipFuncSetAttribute((const void*)route_kernel<TIn, 16, false>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess &&
+           hipFuncSetAttribute((const void*)route_kernel<TIn, 16, true>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
+  }();
+  if (!attr_ok) return PRISM_ERR_LAUNCH;
 #define PRISM_ROUTE_LAUNCH(NT, PARTIAL)                                                          \
   hipLaunchKernelGGL((route_kernel<TIn, NT, PARTIAL>), grid, block,                              \
                      (size_t)(kWavesPerBlock / 2) * NT * 4 * 64 * 8, st, (const TIn*)x, (const TIn*)w,  \
