@@ -122,3 +122,37 @@ def test_large_ragged_batch():
     _check_integers(cfg, inp, o)
     err = _check_sampled_output(cfg, inp, o, 96, seed=11)
     print(f"large batch: sampled out err {err:.3g}")
+
+
+def test_cfg2_full_size_properties_that_hold_at_any_size():
+    """Without the oracle: local partial + remote partial = the layer with every expert hosted
+    (Sec. III-A: remote results are sent back and aggregated), and permuting the tokens
+    permutes the outputs and leaves the activation counts unchanged."""
+    cfg = CONFIGS["cfg2_mixtral_prefill"]
+    inp = make_inputs(cfg, weights="all", threads=16)
+    desc = desc_of(cfg)
+    ws = P.alloc_workspace(desc, cfg.T)
+    wt = weight_table(inp, all_experts=True)
+    x, w_r, bias = to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias)
+
+    def run(xx, mask):
+        o = P.prism_moe_layer(desc, xx, w_r, bias, wt, to_dev(mask), ws)
+        torch.cuda.synchronize()
+        return o
+
+    ones = np.ones(cfg.E, np.uint8)
+    local, remote, full = run(x, inp.mask), run(x, 1 - inp.mask), run(x, ones)
+    assert torch.equal(local.topk_idx, full.topk_idx) and torch.equal(local.counts, full.counts)
+    assert int(local.n_local_remote[0]) == int(remote.n_local_remote[1])
+    assert full.n_local_remote.cpu().tolist() == [cfg.A, 0]
+    summed = to_f32(local.out).astype(np.float64) + to_f32(remote.out)
+    assert rel_err(summed, to_f32(full.out)) <= 2 * TOL[cfg.dtype]
+
+    perm = torch.from_numpy(np.random.default_rng(12).permutation(cfg.T)).cuda()
+    shuffled = run(x[perm].contiguous(), inp.mask)
+    assert torch.equal(shuffled.counts, local.counts)
+    assert torch.equal(shuffled.topk_idx, local.topk_idx[perm])
+    assert torch.equal(shuffled.topk_gate, local.topk_gate[perm])
+    assert shuffled.n_local_remote.cpu().tolist() == local.n_local_remote.cpu().tolist()
+    # rows meet other rows in the MFMA tiles, but every row's sums are formed in the same order
+    assert rel_err(to_f32(shuffled.out), to_f32(local.out[perm])) <= 1e-6
