@@ -84,6 +84,15 @@ typedef enum {
   PRISM_GATES_SOFTMAX_ALL = 1   /* the picked entries of the softmax over all E logits */
 } prism_gate_mode;
 
+/* Memory layout of every expert weight matrix [rows, cols] (w_gate, w_up: [F,H]; w_down: [H,F]).
+ * PRISM_WEIGHTS_BLOCKED64 (bf16 layers only): 64 x 64 element blocks of 8 KiB, blocks stored
+ * row-block major, rows of a block 128 bytes apart; element (r, c) lies at byte
+ *   ((r / 64) * (cols / 64) + c / 64) * 8192 + (r % 64) * 128 + (c % 64) * 2.
+ * A matrix is brought into it once, when the expert is loaded, with prism_pack_weights; the
+ * kernels then fetch contiguous 8 KiB blocks instead of 64- or 128-byte pieces of rows that lie
+ * 8 - 28 KiB apart, which the memory serves a few percent faster.  Results are bit-identical. */
+typedef enum { PRISM_WEIGHTS_ROW_MAJOR = 0, PRISM_WEIGHTS_BLOCKED64 = 1 } prism_weight_layout;
+
 /* Layer description: plain data in HOST memory, passed by const pointer. */
 typedef struct {
   int32_t hidden;            /* H */
@@ -94,6 +103,7 @@ typedef struct {
   int32_t dtype;             /* prism_dtype of x, every weight matrix, y and out */
   int32_t bias_group_tokens; /* 0: bias row 0 for all tokens; else row = t / this */
   int32_t gate_mode;         /* prism_gate_mode: what the k gate values of a token are */
+  int32_t weight_layout;     /* prism_weight_layout of all expert weight matrices */
 } prism_layer_desc;
 
 /*
@@ -260,6 +270,15 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                                     int32_t* remote_offsets, int32_t* n_local_remote,
                                     int64_t* remote_bytes, void* workspace, size_t workspace_bytes,
                                     void* stream, void* const* stage_events);
+
+/*
+ * Re-lays a row-major bf16 matrix [rows, cols] into PRISM_WEIGHTS_BLOCKED64 (see
+ * prism_weight_layout).  rows and cols must be multiples of 64; src and dst are device
+ * buffers of rows * cols * 2 bytes, 16-byte aligned, and must not overlap.  Enqueues one
+ * kernel on `stream`.  Errors: PRISM_ERR_INVALID_ARG (NULL, sizes < 1, misaligned),
+ * PRISM_ERR_UNSUPPORTED (sizes not multiples of 64, or the matrix is 4 GiB or more).
+ */
+prism_status prism_pack_weights(const void* src, int32_t rows, int32_t cols, void* dst, void* stream);
 
 /*
  * Debug helper, NOT asynchronous: copies the pointer tables and the mask back

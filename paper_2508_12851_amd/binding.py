@@ -20,9 +20,10 @@ PRISM_F32, PRISM_BF16 = 0, 1
 SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism_dispatch",
            "prism_expert_ffn", "prism_combine", "prism_moe_layer", "prism_moe_layer_traced",
            "prism_ceiling_mfma_bf16", "prism_ceiling_hbm_read", "prism_pack_remote",
-           "prism_combine_remote", "prism_debug_check_weights")
+           "prism_combine_remote", "prism_debug_check_weights", "prism_pack_weights")
 STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
 GATE_MODES = {"renormalized": 0, "softmax_all": 1}
+WEIGHT_LAYOUTS = {"row_major": 0, "blocked64": 1}
 
 
 class PrismError(RuntimeError):
@@ -32,7 +33,8 @@ class PrismError(RuntimeError):
 class LayerDesc(ctypes.Structure):
     _fields_ = [("hidden", ctypes.c_int32), ("ffn", ctypes.c_int32), ("n_experts", ctypes.c_int32),
                 ("top_k", ctypes.c_int32), ("n_shared", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("bias_group_tokens", ctypes.c_int32), ("gate_mode", ctypes.c_int32)]
+                ("bias_group_tokens", ctypes.c_int32), ("gate_mode", ctypes.c_int32),
+                ("weight_layout", ctypes.c_int32)]
 
 
 class ExpertWeights(ctypes.Structure):
@@ -70,6 +72,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.prism_moe_layer_traced.argtypes = lib.prism_moe_layer.argtypes + [vp]
     lib.prism_pack_remote.argtypes = [dp, vp, vp, vp, i32, vp, vp]
     lib.prism_combine_remote.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.prism_pack_weights.argtypes = [vp, i32, i32, vp, vp]
     lib.prism_debug_check_weights.argtypes = [dp, wp, vp, ctypes.POINTER(i32)]
     lib.prism_ceiling_mfma_bf16.argtypes = [vp, vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.prism_ceiling_hbm_read.argtypes = [vp, sz, vp, i32, vp]
@@ -104,10 +107,10 @@ def _stream(stream: Optional[torch.cuda.Stream]) -> Optional[int]:
 
 def make_desc(hidden: int, ffn: int, n_experts: int, top_k: int, n_shared: int = 0,
               dtype: str = "bf16", bias_group_tokens: int = 0,
-              gate_mode: str = "renormalized") -> LayerDesc:
+              gate_mode: str = "renormalized", weight_layout: str = "row_major") -> LayerDesc:
     return LayerDesc(hidden, ffn, n_experts, top_k, n_shared,
                      PRISM_F32 if dtype == "f32" else PRISM_BF16, bias_group_tokens,
-                     GATE_MODES[gate_mode])
+                     GATE_MODES[gate_mode], WEIGHT_LAYOUTS[weight_layout])
 
 
 def torch_dtype(desc: LayerDesc) -> torch.dtype:
@@ -317,3 +320,12 @@ def prism_debug_check_weights(desc: LayerDesc, weights: WeightTable, local_mask)
     if code != 0:
         what = f"expert {bad.value}" if bad.value >= 0 else "arguments"
         _check(code, f"prism_debug_check_weights ({what})")
+
+
+def prism_pack_weights(w, stream=None) -> torch.Tensor:
+    """Row-major bf16 weight matrix -> the 64 x 64 blocked layout (a new tensor of the same shape)."""
+    rows, cols = w.shape
+    packed = torch.empty_like(w)
+    _check(load_library().prism_pack_weights(_ptr(w), rows, cols, _ptr(packed), _stream(stream)),
+           "prism_pack_weights")
+    return packed

@@ -110,6 +110,19 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const TIO* __restrict__ 
       *reinterpret_cast<const raw_t*>(x + (size_t)t * H + col);
 }
 
+// One 16-byte chunk (8 bf16) per thread from the row-major matrix to its place in the
+// 64 x 64 blocked layout.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const uint4* __restrict__ src, int rows,
+                                                           int cols, uint4* __restrict__ dst) {
+  const int chunks_per_row = cols / 8;
+  const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (long long)rows * chunks_per_row) return;
+  const unsigned r = (unsigned)(gid / chunks_per_row);
+  const unsigned c = (unsigned)(gid - (long long)r * chunks_per_row) * 8;   // first column
+  const size_t byte = ((size_t)(r >> 6) * (cols >> 6) + (c >> 6)) * 8192 + (r & 63u) * 128 + (c & 63u) * 2;
+  dst[byte / 16] = src[gid];
+}
+
 // Same aggregation with y taken from the contraction slices (bf16 layers).  Four
 // columns per thread: a decode batch has few tokens, and the narrower vectors put
 // twice as many workgroups on the machine.  The kernel is a chain of dependent
@@ -197,6 +210,14 @@ prism_status launch_build_inverse(const prism_layer_desc& d, const int32_t* loca
   PRISM_TRY(launch_fill_i32(inv, A, -1, st));
   hipLaunchKernelGGL(scatter_inverse_kernel, dim3(ceil_div(A, 256)), dim3(256), 0, st, local_src,
                      local_offsets, d.n_experts, A, inv);
+  PRISM_CHECK_LAUNCH();
+  return PRISM_OK;
+}
+
+prism_status launch_pack_weights(const void* src, int rows, int cols, void* dst, hipStream_t st) {
+  const long long threads = (long long)rows * (cols / 8);
+  hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                     (const uint4*)src, rows, cols, (uint4*)dst);
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;
 }

@@ -172,6 +172,7 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   g1.a_bytes = (uint32_t)((size_t)T * d.hidden * 2);
   g1.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g1.K = d.hidden; g1.N = d.ffn; g1.top_k = d.top_k; g1.E = d.n_experts;
+  g1.b_blocked = d.weight_layout == PRISM_WEIGHTS_BLOCKED64;
   trace(stage_events, PRISM_STAGE_FFN_UP, 0, st);
   PRISM_TRY((gg::launch_gemm<C1::BM, C1::BN, 2, 2, C1::BK, C1::STAGES, true, false, kRotate>(
       g1, gg::sched_capacity(d, T, C1::BM, nt1), st)));
@@ -186,6 +187,7 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   g2.a_bytes = (uint32_t)((size_t)rows * d.ffn * 2);
   g2.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g2.K = d.ffn; g2.N = d.hidden; g2.top_k = d.top_k; g2.E = d.n_experts;
+  g2.b_blocked = d.weight_layout == PRISM_WEIGHTS_BLOCKED64;
   // every contraction slice must be at least as long as the k-tile ring
   int n_splits = 1;
   if (SPLIT_DOWN) {
@@ -220,6 +222,7 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
   const int A = T * d.top_k;
   const int rows = A + d.n_shared * T;
   if (d.dtype == PRISM_F32) {
+    if (d.weight_layout != PRISM_WEIGHTS_ROW_MAJOR) return PRISM_ERR_UNSUPPORTED;
     F32Args a{(const float*)x, w.w_gate, w.w_up, w.w_down, w.shared_w_gate, w.shared_w_up,
               w.shared_w_down, local_src, local_offsets, (float*)h, (float*)y,
               T, d.hidden, d.ffn, d.n_experts, d.n_shared, d.top_k};

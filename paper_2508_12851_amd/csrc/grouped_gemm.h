@@ -66,6 +66,7 @@ struct GemmArgs {
   int N;                    // output columns (F for GEMM1, H for GEMM2)
   int top_k;
   int E;
+  int b_blocked;            // weights in the 64 x 64 blocked layout (prism.h) instead of row-major
 };
 
 constexpr int kGemmThreads = 256;
@@ -215,6 +216,12 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
                                                it.row_start * 4, 0, 0);
     return r;
   };
+  // Byte offset of weight row n at contraction element 0 (the k offset is added per k-tile):
+  // row-major, or 64 x 64 blocks of 8 KiB laid out row-block major.
+  auto weight_row_offset = [&](uint32_t n) {
+    return p.b_blocked ? (n >> 6) * ((uint32_t)p.K >> 6) * 8192u + (n & 63u) * 128u
+                       : n * (uint32_t)p.K * 2u;
+  };
   auto make_ctx = [&](const Item& it, const Raw& raw) {
     Ctx cx;
     cx.row_start = it.row_start; cx.row_count = it.row_count; cx.nt = it.nt;
@@ -242,10 +249,10 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
         // tile rows [w WN, w WN + WN/2) are gate rows, the next WN/2 the up rows of the same f
         const int w = g0 / WN, within = g0 % WN;
         const int f = min(it.nt * (BN / 2) + w * (WN / 2) + (within % (WN / 2)) + sub, p.N - 1);
-        cx.b_voff[i] = ((uint32_t)f * (uint32_t)p.K + c * 8) * 2;
+        cx.b_voff[i] = weight_row_offset((uint32_t)f) + c * 16;
       } else {
         const int n = min(it.nt * BN + g0 + sub, p.N - 1);
-        cx.b_voff[i] = ((uint32_t)n * (uint32_t)p.K + c * 8) * 2;
+        cx.b_voff[i] = weight_row_offset((uint32_t)n) + c * 16;
       }
     }
     return cx;
@@ -261,7 +268,9 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
       kt_mem += cx.rot;
       if (kt_mem >= KT) kt_mem -= KT;
     }
-    const int koff = (kt_first + kt_mem) * (BK * 2);
+    const int kel = (kt_first + kt_mem) * BK;                 // first contraction element
+    const int koff = kel * 2;
+    const int koff_b = p.b_blocked ? (kel >> 6) * 8192 + (kel & 63) * 2 : koff;
     const __amdgpu_buffer_rsrc_t b0_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)cx.b0, 0, (int)p.b_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t b1_rsrc =
@@ -278,7 +287,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
         const bool up = GATED && (g0 % WN) >= WN / 2;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(up ? b1_rsrc : b0_rsrc,
                                                  (lds_ptr_t)(base + (BM + i * 4 * RPG) * kRowBytes),
-                                                 16, cx.b_voff[i], koff, 0, 0);
+                                                 16, cx.b_voff[i], koff_b, 0, 0);
       }
   };
 

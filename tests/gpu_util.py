@@ -17,21 +17,24 @@ def to_f32(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy()
 
 
-def desc_of(cfg, gate_mode="renormalized"):
-    return P.make_desc(cfg.H, cfg.F, cfg.E, cfg.k, cfg.S, cfg.dtype, cfg.bias_group_tokens, gate_mode)
+def desc_of(cfg, gate_mode="renormalized", weight_layout="row_major"):
+    return P.make_desc(cfg.H, cfg.F, cfg.E, cfg.k, cfg.S, cfg.dtype, cfg.bias_group_tokens, gate_mode,
+                       weight_layout)
 
 
-def weight_table(inp, mask=None, all_experts=False):
-    """Upload hosted experts (None for the others) and the shared experts."""
+def weight_table(inp, mask=None, all_experts=False, blocked=False):
+    """Upload hosted experts (None for the others) and the shared experts; blocked: re-laid
+    into the 64 x 64 blocked layout by the library's own pack kernel."""
     c = inp.cfg
     mask = inp.mask if mask is None else mask
+    up = (lambda w: P.prism_pack_weights(to_dev(w))) if blocked else to_dev
     experts = []
     for e in range(c.E):
         if all_experts or mask[e]:
-            experts.append(tuple(to_dev(w) for w in inp.expert(e)))
+            experts.append(tuple(up(w) for w in inp.expert(e)))
         else:
             experts.append(None)
-    shared = [tuple(to_dev(w) for w in inp.shared(s)) for s in range(c.S)]
+    shared = [tuple(up(w) for w in inp.shared(s)) for s in range(c.S)]
     return P.WeightTable(experts, shared)
 
 
@@ -58,8 +61,9 @@ def rel_err(a, ref):
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
-def run_layer(cfg, inp, mask=None, wt=None, ws=None, gate_mode="renormalized", **kw):
-    desc = desc_of(cfg, gate_mode)
+def run_layer(cfg, inp, mask=None, wt=None, ws=None, gate_mode="renormalized",
+              weight_layout="row_major", **kw):
+    desc = desc_of(cfg, gate_mode, weight_layout)
     ws = P.alloc_workspace(desc, cfg.T) if ws is None else ws
     mask = inp.mask if mask is None else mask
     wt = weight_table(inp, mask) if wt is None else wt
