@@ -71,15 +71,12 @@ struct GemmArgs {
 
 constexpr int kGemmThreads = 256;
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
 // Schedule entries and pointer tables are written before the kernel starts and
 // never during it; reading them through the constant address space lets the
 // compiler use scalar loads, which the vector-memory counter does not see.
 typedef const __attribute__((address_space(4))) int4* const_int4_ptr;
 typedef const __attribute__((address_space(4))) int32_t* const_int_ptr;
 typedef const void* const __attribute__((address_space(4)))* const_ptr_table;
-constexpr int kBufferFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
-constexpr uint32_t kOutOfRange = 0xFFFFFF00u;   // above every operand size (those stay below 0xFFFF0000)
 
 // silu(z) = z / (1 + e^-z) with the hardware exp2 and reciprocal (each within 1 ulp;
 // the result is rounded to bf16 right after).
@@ -93,10 +90,6 @@ __device__ __forceinline__ float silu(float z) {
 // that share (row * row_bytes) mod 256 get different keys.
 template <int BK> __device__ __forceinline__ int swizzle_key(int row) {
   return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
-}
-
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 // BM x BN output tile per workgroup; BN counts weight rows in the tile (for

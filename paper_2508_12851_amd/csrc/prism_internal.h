@@ -190,6 +190,16 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// Direct global -> LDS loads (buffer_load_dwordx4 ... lds): raw buffer resources whose size
+// makes a lane offset at or above it read zeros (the scalar offset of a load is not part of
+// that check), and the vector-memory counter the loads are awaited with.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+constexpr int kBufferFlags = 0x00020000;        // raw buffer, 32-bit data format (gfx9 family)
+constexpr uint32_t kOutOfRange = 0xFFFFFF00u;   // above every operand size (those stay below 0xFFFF0000)
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
   return __uint_as_float((uint32_t)b << 16);
 }

@@ -45,9 +45,91 @@ __device__ __forceinline__ void load8(const uint16_t* p, float (&v)[8]) {
   v[4] = bf16_lo(a.z); v[5] = bf16_hi(a.z); v[6] = bf16_lo(a.w); v[7] = bf16_hi(a.w);
 }
 
-// From the complete fp64 logit tile of 16 tokens (held by one wavefront in the
-// accumulator layout of v_mfma_f64_16x16x4) to top-k indices and gates.  Run by one
-// whole wavefront.  s_counts (LDS, may be NULL) receives +1 per selected expert.
+// Router-bias entries of token t for the experts 16 n + r this lane holds (0 where there is
+// none: no bias, expert past E, token past T).
+template <int NT>
+__device__ __forceinline__ void load_bias_group(const float* __restrict__ bias, int t, int T, int E,
+                                                int bias_group_tokens, float (&b)[NT]) {
+  const int r = threadIdx.x & 15;
+  const int row = bias_group_tokens > 0 ? t / bias_group_tokens : 0;
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+    const int e = n * 16 + r;
+    b[n] = bias != nullptr && e < E && t < T ? bias[(size_t)row * E + e] : 0.f;
+  }
+}
+
+// From the complete fp64 logits of one token per 16-lane group (lane r of the group holds
+// experts 16 n + r of token t) to that token's top-k indices and gates.  Run by a whole
+// wavefront.  has_bias: add b (from load_bias_group) after the one rounding to fp32.
+// s_counts (LDS, may be NULL) receives +1 per selected expert.
+template <int NT>
+__device__ __forceinline__ void finish_group(const double (&s)[NT], const float (&b)[NT],
+                                             bool has_bias, int t, int T, int E, int k, int gate_mode,
+                                             float* __restrict__ logits, int32_t* topk_idx,
+                                             float* __restrict__ topk_gate, int* s_counts) {
+  const int r = threadIdx.x & 15;
+  // ---- one rounding to fp32, then the fp32 bias add --------------------------
+  float lg[NT];
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+    const int e = n * 16 + r;
+    float val = (float)s[n];
+    if (e < E && t < T) {
+      if (has_bias) val = val + b[n];
+      if (logits != nullptr) logits[(size_t)t * E + e] = val;
+    } else if (e >= E) {
+      val = -INFINITY;
+    }
+    lg[n] = val;
+  }
+
+  // ---- top-k: k rounds of arg-max over (logit, expert index) with xor-shuffles inside the
+  // group; equal logits resolve to the lower expert index.
+  float vals[NT];
+#pragma unroll
+  for (int n = 0; n < NT; ++n) vals[n] = lg[n];
+  float sel0 = 0.f, mysel = 0.f;
+  int myidx = 0;
+  for (int j = 0; j < k; ++j) {
+    float best = vals[0];
+    int bidx = r;
+#pragma unroll
+    for (int n = 1; n < NT; ++n)
+      if (vals[n] > best) { best = vals[n]; bidx = n * 16 + r; }
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(best, off);
+      const int oi = __shfl_xor(bidx, off);
+      if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
+    }
+    // every lane of the group holds the winner; its owner retires it
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+      if (bidx == n * 16 + r) vals[n] = -INFINITY;
+    if (j == 0) sel0 = best;
+    if (r == j) { mysel = best; myidx = bidx; }
+  }
+  // gates: softmax over the k picked logits, or the picked entries of the softmax over
+  // all experts; lane r < k owns slot r, sel0 is the token's largest logit
+  double w = r < k ? exp((double)mysel - (double)sel0) : 0.0;
+  double sum = w;
+  if (gate_mode == PRISM_GATES_SOFTMAX_ALL) {
+    sum = 0.0;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) sum += exp((double)lg[n] - (double)sel0);   // exp(-inf) = 0 past E
+  }
+#pragma unroll
+  for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+  if (r < k && t < T) {
+    topk_idx[(size_t)t * k + r] = myidx;
+    topk_gate[(size_t)t * k + r] = (float)(w / sum);
+    if (s_counts != nullptr) atomicAdd(&s_counts[myidx], 1);
+  }
+}
+
+// The same for a tile of 16 tokens held by one wavefront in the accumulator layout of
+// v_mfma_f64_16x16x4: register v of lane (r, q) is token 4 v + q, expert 16 n + r.
 // v_mask (wave-uniform): bit v set = handle the four tokens 4v + q of the tile, so
 // several wavefronts can share one tile's work.
 template <int NT>
@@ -56,81 +138,18 @@ __device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0, in
                                             int bias_group_tokens, int gate_mode,
                                             float* __restrict__ logits, int32_t* topk_idx,
                                             float* __restrict__ topk_gate, int* s_counts) {
-  const int lane = threadIdx.x & 63;
-  const int r = lane & 15;
-  const int q = lane >> 4;
-
-  // ---- one rounding to fp32, then the fp32 bias add --------------------------
-  // Accumulator register v of lane (r, q) is token 4v + q, expert 16n + r.
-  float lg[NT][4];
-#pragma unroll
-  for (int n = 0; n < NT; ++n) {
-    const int e = n * 16 + r;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      if (!((v_mask >> v) & 1)) continue;
-      const int t = tok0 + 4 * v + q;
-      float val = (float)acc[n][v];
-      if (e < E && t < T) {
-        if (bias != nullptr) {
-          const int row = bias_group_tokens > 0 ? t / bias_group_tokens : 0;
-          val = val + bias[(size_t)row * E + e];
-        }
-        if (logits != nullptr) logits[(size_t)t * E + e] = val;
-      } else if (e >= E) {
-        val = -INFINITY;
-      }
-      lg[n][v] = val;
-    }
-  }
-
-  // ---- top-k: each 16-lane group owns one token per register index v ---------
-  // k rounds of arg-max over (logit, expert index) with xor-shuffles inside the
-  // group; equal logits resolve to the lower expert index.
+  const int q = (threadIdx.x & 63) >> 4;
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     if (!((v_mask >> v) & 1)) continue;
     const int t = tok0 + 4 * v + q;
-    float vals[NT];
+    double s[NT];
+    float b[NT];
 #pragma unroll
-    for (int n = 0; n < NT; ++n) vals[n] = lg[n][v];
-    float sel0 = 0.f, mysel = 0.f;
-    int myidx = 0;
-    for (int j = 0; j < k; ++j) {
-      float best = vals[0];
-      int bidx = r;
-#pragma unroll
-      for (int n = 1; n < NT; ++n)
-        if (vals[n] > best) { best = vals[n]; bidx = n * 16 + r; }
-#pragma unroll
-      for (int off = 8; off >= 1; off >>= 1) {
-        const float ov = __shfl_xor(best, off);
-        const int oi = __shfl_xor(bidx, off);
-        if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
-      }
-      // every lane of the group holds the winner; its owner retires it
-#pragma unroll
-      for (int n = 0; n < NT; ++n)
-        if (bidx == n * 16 + r) vals[n] = -INFINITY;
-      if (j == 0) sel0 = best;
-      if (r == j) { mysel = best; myidx = bidx; }
-    }
-    // gates: softmax over the k picked logits, or the picked entries of the softmax over
-    // all experts; lane r < k owns slot r, sel0 is the token's largest logit
-    double w = r < k ? exp((double)mysel - (double)sel0) : 0.0;
-    double sum = w;
-    if (gate_mode == PRISM_GATES_SOFTMAX_ALL) {
-      sum = 0.0;
-#pragma unroll
-      for (int n = 0; n < NT; ++n) sum += exp((double)lg[n][v] - (double)sel0);   // exp(-inf) = 0 past E
-    }
-#pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
-    if (r < k && t < T) {
-      topk_idx[(size_t)t * k + r] = myidx;
-      topk_gate[(size_t)t * k + r] = (float)(w / sum);
-      if (s_counts != nullptr) atomicAdd(&s_counts[myidx], 1);
-    }
+    for (int n = 0; n < NT; ++n) s[n] = acc[n][v];
+    load_bias_group<NT>(bias, t, T, E, bias_group_tokens, b);
+    finish_group<NT>(s, b, bias != nullptr, t, T, E, k, gate_mode, logits, topk_idx, topk_gate,
+                     s_counts);
   }
 }
 
@@ -245,6 +264,208 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
   }
 }
 
+// Router for bf16 batches of more than 64 tokens and at most 64 experts: operands staged
+// through LDS.
+//
+// Loading operands from global memory straight in the MFMA layout (route_kernel) makes every
+// quarter of a load instruction touch 16 rows, 16 bytes of each, and the vector cache then
+// bounds the kernel (64 cache-line lookups per instruction; the fp64 matrix cores were busy
+// 42 % of the time at 8192 tokens x 60 experts).  Here a wavefront brings its 32-element
+// slice of 16 rows with one buffer_load_dwordx4 ... lds whose lanes cover each row's 64 bytes
+// contiguously (lane l: row l / 4, 16 lookups per instruction), into LDS that is private to
+// the wavefront, and reads it back in the MFMA layout (lane (r, q): row r, chunk q).  A
+// 1 KiB block holds 16 rows x 4 chunks of 16 bytes; chunk c of row r sits in slot
+// (c + r / 4) % 4 of the row, which the global side provides by fetching chunk
+// (l % 4 - l / 16) % 4 into lane l, so that the 16 rows a quarter-wavefront reads fall into
+// 16 different 16-byte slots of the 256-byte bank window.
+// A workgroup takes TMB tiles of 16 tokens (two when there are more tiles than compute
+// units, which halves the router-weight traffic); its 8 wavefronts split the hidden
+// dimension into eighths, each with kDepth slices in flight (no workgroup barrier in the
+// loop).  The partial tiles are then summed in wavefront order, each
+// finishing wavefront taking four tokens of one tile.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int NT, int TMB>
+struct StagedCfg {
+  static constexpr int kBlocks = TMB + NT;                       // 1 KiB blocks per slice
+  static constexpr int kFit = (96 * 1024) / (kWavesPerBlock * kBlocks * 1024);
+  static constexpr int kDepth = kFit < 4 ? kFit : 4;             // slices in flight per wavefront
+  static constexpr int kStageBytes = kWavesPerBlock * kDepth * kBlocks * 1024;
+  static constexpr int kReduceBytes = kWavesPerBlock * TMB * NT * 4 * 64 * 8;
+  static constexpr int kLdsBytes = kStageBytes > kReduceBytes ? kStageBytes : kReduceBytes;
+  static_assert(kDepth >= 2, "the next slice must be in flight during the MFMAs of this one");
+};
+
+template <int NT, int TMB>
+__global__ __launch_bounds__(kWavesPerBlock* kWave) void route_staged_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router,
+    const float* __restrict__ bias, int T, int H, int E, int k, int bias_group_tokens, int gate_mode,
+    float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate,
+    int32_t* __restrict__ counts, unsigned long long* __restrict__ counts_accum) {
+#if defined(__HIP_DEVICE_COMPILE__)   // buffer resources exist in device code only
+  using C = StagedCfg<NT, TMB>;
+  constexpr int EP = NT * 16;
+  constexpr int kBlocks = C::kBlocks, kDepth = C::kDepth;
+  __shared__ int s_counts[EP];
+  extern __shared__ __align__(16) uint8_t smem[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = lane & 15;
+  const int q = lane >> 4;
+  const int tok0 = blockIdx.x * (kTokPerBlock * TMB);
+
+  for (int e = threadIdx.x; e < EP; e += blockDim.x) s_counts[e] = 0;
+  __syncthreads();
+
+  // ---- global side: lane l fetches row l / 4 of each block, chunk (l % 4 - l / 16) % 4 ----
+  const int lrow = lane >> 2;
+  const int chunk = ((lane & 3) - (lane >> 4)) & 3;
+  uint32_t voff[kBlocks];
+#pragma unroll
+  for (int b = 0; b < TMB; ++b) {
+    const int t = tok0 + b * kTokPerBlock + lrow;
+    voff[b] = t < T ? ((uint32_t)t * (uint32_t)H + chunk * 8) * 2u : kOutOfRange;
+  }
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+    const int e = n * 16 + lrow;
+    voff[TMB + n] = e < E ? ((uint32_t)e * (uint32_t)H + chunk * 8) * 2u : kOutOfRange;
+  }
+  const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)x, 0, (int)((uint32_t)T * (uint32_t)H * 2u), kBufferFlags);
+  const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)w_router, 0, (int)((uint32_t)E * (uint32_t)H * 2u), kBufferFlags);
+  uint8_t* const wave_base = smem + wave * (kDepth * kBlocks * 1024);
+  const int n_slices = (H + 31) / 32;
+  // Fills ring position `buf` with slice s (hidden elements 32 s ..): rows or chunks past
+  // the end, and whole slices past the last one, arrive as zeros.  Always kBlocks loads, so
+  // the vector-memory counter can be awaited with a constant.
+  auto issue = [&](int s, int buf) {
+    const bool live = s < n_slices;                       // wavefront-uniform
+    const int h0 = live ? s * 32 : 0;
+    const bool inside = live && h0 + chunk * 8 < H;
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(b < TMB ? x_rsrc : w_rsrc,
+                                               (lds_ptr_t)(wave_base + (buf * kBlocks + b) * 1024), 16,
+                                               inside ? voff[b] : kOutOfRange, h0 * 2, 0, 0);
+  };
+
+  // After the GEMM this wavefront finishes token 4 v + q of tile b; its bias entries are
+  // fetched now, so that their latency is not paid at the end.
+  const int b_fin = wave >> 2, v_fin = wave & 3;
+  const int t_fin = tok0 + b_fin * kTokPerBlock + 4 * v_fin + q;
+  float bias_fin[NT];
+  load_bias_group<NT>(bias, b_fin < TMB ? t_fin : T, T, E, bias_group_tokens, bias_fin);
+
+  // ---- router GEMM on the fp64 matrix cores -----------------------------------------
+  f64x4 acc[TMB][NT];
+#pragma unroll
+  for (int b = 0; b < TMB; ++b)
+#pragma unroll
+    for (int n = 0; n < NT; ++n) acc[b][n] = f64x4{0.0, 0.0, 0.0, 0.0};
+
+  // Wavefront w owns the w-th eighth of the slices and walks it cyclically from a phase that
+  // keeps the 8 wavefronts 512 bytes (or, where an eighth is a multiple of 4 KiB, 256 bytes)
+  // apart modulo 4 KiB: every row of x and of the router weights starts a multiple of 2 H
+  // bytes from the base, so all rows at one hidden offset sit in the same memory channels,
+  // and all workgroups run in step.  (With each wavefront taking every eighth slice, the
+  // whole chip read a 512-byte column window at any time, and the L2 channels holding it
+  // bounded the kernel.)  The order is the same for every workgroup, so a token's logits do
+  // not depend on where in the batch it sits.
+  const int seg = (n_slices + kWavesPerBlock - 1) / kWavesPerBlock;
+  const int first = wave * seg;
+  const int n_mine = max(0, min(seg, n_slices - first));
+  const int phase = n_mine > 0 ? (4 * ((wave * seg) >> 6)) % n_mine : 0;
+  auto slice_of = [&](int i) {   // i-th slice this wavefront multiplies; past its last: none
+    if (i >= n_mine) return n_slices;
+    const int j = i + phase;
+    return first + (j >= n_mine ? j - n_mine : j);
+  };
+#pragma unroll
+  for (int d = 0; d < kDepth; ++d) issue(slice_of(d), d);
+  // LDS byte address of row r, chunk q of this wavefront's first block
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_ptr_t)wave_base +
+                            (uint32_t)((r * 4 + ((q + (r >> 2)) & 3)) * 16);
+  int buf = 0;
+  for (int i = 0; i < n_mine; ++i) {
+    wait_vmcnt<(kDepth - 1) * kBlocks>();                 // slice i has landed
+    // The LDS reads are issued from assembly: for reads the compiler sees, it waits until
+    // every direct-to-LDS load in flight has landed, the prefetched slices included.
+    const uint32_t sb = lds_base + buf * (kBlocks * 1024);
+    u32x4 xa[TMB], wb[NT];
+#pragma unroll
+    for (int b = 0; b < TMB; ++b)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(xa[b]) : "v"(sb), "n"(b * 1024));
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(wb[n]) : "v"(sb), "n"((TMB + n) * 1024));
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // read before the refill may overwrite it
+#pragma unroll
+    for (int b = 0; b < TMB; ++b) asm volatile("" : "+v"(xa[b]));   // no use moves above the wait
+#pragma unroll
+    for (int n = 0; n < NT; ++n) asm volatile("" : "+v"(wb[n]));
+    issue(slice_of(i + kDepth), buf);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      auto element = [&](const u32x4& v) {
+        const unsigned w = v[j >> 1];
+        return (double)((j & 1) ? bf16_hi(w) : bf16_lo(w));
+      };
+      double a[TMB];
+#pragma unroll
+      for (int b = 0; b < TMB; ++b) a[b] = element(xa[b]);
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+        const double bw = element(wb[n]);
+#pragma unroll
+        for (int b = 0; b < TMB; ++b)
+          acc[b][n] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[b], bw, acc[b][n], 0, 0, 0);
+      }
+    }
+    buf = buf + 1 == kDepth ? 0 : buf + 1;
+  }
+  wait_vmcnt<0>();   // the zero-filled refills past the end must land before the LDS is reused
+  __syncthreads();
+
+  // ---- partial tiles -> LDS as [wavefront][tile][n][v][lane]; summed in wavefront order ----
+  double* part = reinterpret_cast<double*>(smem);
+#pragma unroll
+  for (int b = 0; b < TMB; ++b)
+#pragma unroll
+    for (int n = 0; n < NT; ++n)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        part[((((size_t)wave * TMB + b) * NT + n) * 4 + v) * 64 + lane] = acc[b][n][v];
+  __syncthreads();
+  if (b_fin < TMB) {
+    double sum[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+      double s = 0.0;
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w)
+        s += part[((((size_t)w * TMB + b_fin) * NT + n) * 4 + v_fin) * 64 + lane];
+      sum[n] = s;
+    }
+    finish_group<NT>(sum, bias_fin, bias != nullptr, t_fin, T, E, k, gate_mode, logits, topk_idx,
+                     topk_gate, counts != nullptr ? s_counts : nullptr);
+  }
+  if (counts == nullptr) return;   // the caller derives the counts from the dispatch histogram
+
+  // ---- per-expert activation counts -----------------------------------------
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    const int c = s_counts[e];
+    if (c != 0) {
+      atomicAdd(&counts[e], c);
+      if (counts_accum != nullptr) atomicAdd(&counts_accum[e], (unsigned long long)c);
+    }
+  }
+#endif
+}
+
 __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -312,6 +533,45 @@ __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
 // trip of the 8 wavefronts covers, at most kRouteMaxHSplit slices.
 inline int route_h_span(int H) { return 256 * ceil_div(H, 256 * kRouteMaxHSplit); }
 
+// Whether route_staged_kernel serves this call (else route_kernel does).
+inline bool staged_router_applies(const prism_layer_desc& d, int T) {
+  return d.dtype == PRISM_BF16 && T > kDecodeMaxTokens && route_col_tiles(d.n_experts) <= 4 &&
+         (uint64_t)T * d.hidden * 2 < 0xFFFF0000ull;
+}
+
+template <int NT, int TMB>
+prism_status launch_staged_one(const prism_layer_desc& d, const void* x, const void* w,
+                               const float* bias, int T, float* logits, int32_t* idx, float* gate,
+                               int32_t* counts, int64_t* accum, hipStream_t st) {
+  using C = StagedCfg<NT, TMB>;
+  // more than 64 KiB of dynamic LDS: raised once per instantiation (thread-safe local static)
+  static const bool attr_ok =
+      hipFuncSetAttribute((const void*)route_staged_kernel<NT, TMB>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes) == hipSuccess;
+  if (!attr_ok) return PRISM_ERR_LAUNCH;
+  hipLaunchKernelGGL((route_staged_kernel<NT, TMB>), dim3(ceil_div(T, kTokPerBlock * TMB)),
+                     dim3(kWavesPerBlock * kWave), (size_t)C::kLdsBytes, st, (const uint16_t*)x,
+                     (const uint16_t*)w, bias, T, d.hidden, d.n_experts, d.top_k,
+                     d.bias_group_tokens, d.gate_mode, logits, idx, gate, counts,
+                     (unsigned long long*)accum);
+  PRISM_CHECK_LAUNCH();
+  return PRISM_OK;
+}
+
+prism_status launch_staged(const prism_layer_desc& d, const void* x, const void* w, const float* bias,
+                           int T, float* logits, int32_t* idx, float* gate, int32_t* counts,
+                           int64_t* accum, hipStream_t st) {
+  const int nt = route_col_tiles(d.n_experts);
+  const bool two = ceil_div(T, kTokPerBlock) > 256;   // more token tiles than compute units
+#define PRISM_STAGED_CASE(NT)                                                                     \
+  return two ? launch_staged_one<NT, 2>(d, x, w, bias, T, logits, idx, gate, counts, accum, st)   \
+             : launch_staged_one<NT, 1>(d, x, w, bias, T, logits, idx, gate, counts, accum, st)
+  if (nt <= 1) PRISM_STAGED_CASE(1);
+  if (nt <= 2) PRISM_STAGED_CASE(2);
+  PRISM_STAGED_CASE(4);
+#undef PRISM_STAGED_CASE
+}
+
 template <typename TIn>
 prism_status launch_typed(const prism_layer_desc& d, const void* x, const void* w, const float* bias,
                           int T, float* logits, int32_t* idx, float* gate, int32_t* counts,
@@ -371,6 +631,9 @@ prism_status launch_route(const prism_layer_desc& d, const void* x, const void* 
   if (d.dtype == PRISM_F32)
     return launch_typed<float>(d, x, w_router, bias, T, logits, topk_idx, topk_gate, counts,
                                counts_accum, nullptr, st);
+  if (staged_router_applies(d, T))
+    return launch_staged(d, x, w_router, bias, T, logits, topk_idx, topk_gate, counts, counts_accum,
+                         st);
   return launch_typed<uint16_t>(d, x, w_router, bias, T, logits, topk_idx, topk_gate, counts,
                                 counts_accum, nullptr, st);
 }

@@ -99,6 +99,45 @@ def test_route_wide_expert_counts_and_ties(E, k, T):
     assert np.max(np.abs(got.topk_gate.cpu().numpy() - ref.topk_gate)) <= 1e-6
 
 
+def _bf16_round(a):
+    return torch.from_numpy(a).bfloat16().float().numpy()
+
+
+# bf16 batches of more than 64 tokens with at most 64 experts take the router that stages its
+# operands through LDS: hidden sizes that end inside a 32-element slice or leave wavefronts
+# without a slice, every column-tile count, one and two token tiles per workgroup with ragged
+# ends, the phase-shifted slice orders of H = 4096 and 8192, both gate conventions
+@pytest.mark.parametrize("T,H,E,k,bgt,gates", [
+    (65, 72, 5, 2, 0, "renormalized"), (100, 1000, 24, 3, 32, "renormalized"),
+    (300, 8, 33, 4, 0, "softmax_all"), (4200, 264, 64, 6, 512, "renormalized"),
+    (4500, 2048, 60, 4, 512, "softmax_all"), (130, 4096, 8, 2, 0, "renormalized"),
+    (70, 8192, 16, 2, 0, "renormalized")])
+def test_route_bf16_prefill_shapes(T, H, E, k, bgt, gates):
+    rng = np.random.default_rng(T + H + E)
+    x = _bf16_round(rng.standard_normal((T, H)).astype(np.float32))
+    w = _bf16_round((rng.standard_normal((E, H)) / np.sqrt(H)).astype(np.float32))
+    w[E - 1] = w[0]                                        # exact ties between experts 0 and E - 1
+    G = -(-T // bgt) if bgt else 1
+    bias = rng.standard_normal((G, E)).astype(np.float32)
+    bias[:, E - 1] = bias[:, 0]
+    ref = O.route(x, w, bias, k, bgt, renormalize=gates == "renormalized")
+    desc = P.make_desc(H, 64, E, k, 0, "bf16", bgt, gates)
+    acc = torch.zeros(E, dtype=torch.int64, device="cuda")
+    xd, wd = (torch.from_numpy(a).bfloat16().cuda() for a in (x, w))
+    got = P.prism_route(desc, xd, wd, to_dev(bias), counts_accum=acc)
+    torch.cuda.synchronize()
+    logits = got.logits.cpu().numpy()
+    assert np.array_equal(got.topk_idx.cpu().numpy(), ref.topk_idx)
+    assert np.array_equal(got.counts.cpu().numpy(), ref.counts)
+    assert np.array_equal(acc.cpu().numpy(), ref.counts.astype(np.int64))
+    assert np.max(np.abs(logits - ref.logits)) <= 1e-6 * max(1.0, np.max(np.abs(ref.logits)))
+    assert np.max(np.abs(got.topk_gate.cpu().numpy() - ref.topk_gate)) <= 1e-6
+    # a token's routing does not depend on where in the batch it sits: reversed batch, no bias groups
+    if bgt == 0:
+        rev = P.prism_route(desc, xd.flip(0).contiguous(), wd, to_dev(bias))
+        assert torch.equal(rev.logits.flip(0), got.logits) and torch.equal(rev.topk_idx.flip(0), got.topk_idx)
+
+
 def test_route_zero_tokens_and_no_bias():
     desc = P.make_desc(64, 64, 8, 2, 0, "f32", 0)
     x = torch.empty((0, 64), device="cuda")
