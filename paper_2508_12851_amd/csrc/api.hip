@@ -236,12 +236,13 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                            nullptr, st));
     trace(ev, PRISM_STAGE_ROUTE, 1, st);
     trace(ev, PRISM_STAGE_DISPATCH, 0, st);
+    bool schedules_built = false;
     PRISM_TRY(launch_dispatch(*desc, topk_idx, local_mask, T, ws.local_src, ws.local_offsets,
                               remote_src, remote_offsets, n_local_remote, remote_bytes, ws.inv,
-                              ws.block_hist, counts, counts_accum, st));
+                              ws.block_hist, counts, counts_accum, st, ws.tiles, &schedules_built));
     trace(ev, PRISM_STAGE_DISPATCH, 1, st);
     PRISM_TRY(launch_expert_ffn(*desc, x, *weights, ws.local_src, ws.local_offsets, T, ws.y, ws.h,
-                                ws.tiles, ws.part, st, ev, &n_splits));
+                                ws.tiles, ws.part, st, ev, &n_splits, schedules_built));
   }
   trace(ev, PRISM_STAGE_COMBINE, 0, st);
   PRISM_TRY(launch_combine(*desc, ws.y, ws.inv, topk_gate, T, out, st, ws.part, n_splits));

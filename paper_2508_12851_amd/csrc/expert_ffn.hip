@@ -254,7 +254,7 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
     // contraction at a different k-tile: at any moment the workgroups then read
     // different column ranges of the weight rows, whose power-of-two pitch would
     // otherwise send them all to the same few memory channels.
-    // (decode_schedule_shapes() below states the tile shapes of both variants)
+    // (ffn_schedule_shapes() below states the tile shapes of all variants)
     if (d.hidden >= 192 && d.ffn >= 192)
       return run_bf16_ffn<TileCfg<64, 128, 64, 4>, TileCfg<64, 128, 64, 4>, true>(
           d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
@@ -270,9 +270,12 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
       d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
 }
 
-void decode_schedule_shapes(const prism_layer_desc& d, int* bm1, int* nt1, int* bm2, int* nt2) {
-  *bm1 = 64; *nt1 = ceil_div(d.ffn, 128 / 2);
-  *bm2 = 64; *nt2 = ceil_div(d.hidden, 128);
+bool ffn_schedule_shapes(const prism_layer_desc& d, int T, int* bm1, int* nt1, int* bm2, int* nt2) {
+  const bool decode = T <= kDecodeMaxTokens;
+  const int bm = decode ? 64 : 256, bn = decode ? 128 : 256;   // both ring depths share the tile
+  *bm1 = bm; *nt1 = ceil_div(d.ffn, bn / 2);
+  *bm2 = bm; *nt2 = ceil_div(d.hidden, bn);
+  return decode;
 }
 
 }  // namespace prism

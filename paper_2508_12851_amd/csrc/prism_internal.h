@@ -114,13 +114,16 @@ prism_status launch_route(const prism_layer_desc& d, const void* x, const void* 
                           hipStream_t st);
 
 // counts NULL: no activation counts from the router (launch_dispatch can supply them).
-// inv, counts, counts_accum of launch_dispatch may be NULL.
+// inv, counts, counts_accum of launch_dispatch may be NULL.  tiles given (bf16 layers): the
+// launch that places the assignments may also build the two GEMM schedules of
+// launch_expert_ffn there; *schedules_built says whether it did.
 prism_status launch_dispatch(const prism_layer_desc& d, const int32_t* topk_idx,
                              const uint8_t* mask, int T, int32_t* local_src,
                              int32_t* local_offsets, int32_t* remote_src, int32_t* remote_offsets,
                              int32_t* n_local_remote, int64_t* remote_bytes, int32_t* inv,
                              int32_t* block_hist, int32_t* counts, int64_t* counts_accum,
-                             hipStream_t st);
+                             hipStream_t st, int32_t* tiles = nullptr,
+                             bool* schedules_built = nullptr);
 
 // schedules_built: the two schedules in tiles already exist (decode front end).
 // deferred_splits NULL: y holds the finished expert outputs.  Otherwise the decode path leaves
@@ -148,9 +151,10 @@ prism_status launch_decode_front_end(const prism_layer_desc& d, const void* x, c
                                      int64_t* remote_bytes, int32_t* inv, double* route_part,
                                      int32_t* tiles, hipStream_t st, void* const* stage_events);
 
-// Tile shapes of the decode path's two grouped GEMMs (row tile, column tiles), which the
-// front end needs to build their schedules.
-void decode_schedule_shapes(const prism_layer_desc& d, int* bm1, int* nt1, int* bm2, int* nt2);
+// Tile shapes of the two grouped GEMMs of launch_expert_ffn for a bf16 batch of T tokens (row
+// tile, column tiles), which whoever builds their schedules needs; returns whether the
+// schedules deal their items to the XCDs one by one (decode batches).
+bool ffn_schedule_shapes(const prism_layer_desc& d, int T, int* bm1, int* nt1, int* bm2, int* nt2);
 
 // Records stage_events[2 * stage + end] on st when tracing is on and the pair is set.
 static inline void trace(void* const* ev, int stage, int end, hipStream_t st) {

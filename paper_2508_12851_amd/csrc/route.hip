@@ -522,8 +522,8 @@ __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
                     nullptr, topk_idx, topk_gate, nullptr);
   }
   __syncthreads();   // topk_idx is complete and visible to the whole workgroup
-  dispatch_dev::dispatch_scatter_block<true>(topk_idx, T * k, E, mask, nullptr, 0, o, local_src,
-                                             remote_src, inv);
+  dispatch_dev::dispatch_place_block<false>(topk_idx, T * k, E, mask, nullptr, 1, 1, 0, o, local_src,
+                                            remote_src, inv);
   __syncthreads();   // local_offsets (written by the split) is visible to the whole workgroup
   const gg::SchedParams p[2] = {p0, p1};
   gg::build_schedules_block<2>(o.local_offsets, E, S, T, T * k, p);
@@ -661,7 +661,7 @@ prism_status launch_decode_front_end(const prism_layer_desc& d, const void* x, c
   const dispatch_dev::SplitOut o{local_offsets, remote_offsets, n_local_remote, remote_bytes, counts,
                                  (unsigned long long*)counts_accum, d.hidden * elem_size(d.dtype)};
   int bm1, nt1, bm2, nt2;
-  decode_schedule_shapes(d, &bm1, &nt1, &bm2, &nt2);
+  ffn_schedule_shapes(d, T, &bm1, &nt1, &bm2, &nt2);
   const gg::SchedParams p0{bm1, nt1, gg::sched_capacity(d, T, bm1, nt1), tiles, 1};
   const gg::SchedParams p1{bm2, nt2, gg::sched_capacity(d, T, bm2, nt2),
                            tiles + tile_table_ints(d, T), 1};

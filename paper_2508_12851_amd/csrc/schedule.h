@@ -65,12 +65,15 @@ __device__ __forceinline__ PartOf part_of(int i, int count, int part_max) {
 // Builds NS (1 or 2) schedules of the same row groups side by side; called by every
 // thread of a workgroup (any size that is a multiple of 64).  Inside, only LDS data
 // crosses between threads, so the barriers do not wait for the global stores.
-// local_offsets may have been written earlier in the same kernel by this workgroup
-// (with a __syncthreads() in between), hence no __restrict__ on it.
+// local_offsets (global memory or LDS) may have been written earlier in the same kernel by
+// this workgroup (with a barrier in between), hence no __restrict__ on it.
+// Several workgroups can share the work: workgroup `part` of `n_parts` writes every
+// n_parts-th group of blockDim.x items, part 0 also the header.
 template <int NS>
 __device__ __forceinline__ void build_schedules_block(const int32_t* local_offsets, int E, int S,
                                                       int T, int A_total,
-                                                      const SchedParams (&p)[NS]) {
+                                                      const SchedParams (&p)[NS], int part = 0,
+                                                      int n_parts = 1) {
   __shared__ int s_rows[kMaxGroups], s_row0[kMaxGroups];
   __shared__ int s_start[NS][kMaxGroups + 1];            // first row tile of group g
   const int G = E + S;
@@ -101,9 +104,11 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
     s_start[s][G] = run;
     const unsigned total = (unsigned)run * (unsigned)ps.n_ntiles;
     const unsigned per_xcd = (total + kXcds - 1) / kXcds;
-    ps.sched[0] = run;
-    ps.sched[1] = ps.capacity;
-    for (unsigned x = 0; x < (unsigned)kXcds; ++x) {
+    if (part == 0) {
+      ps.sched[0] = run;
+      ps.sched[1] = ps.capacity;
+    }
+    for (unsigned x = 0; part == 0 && x < (unsigned)kXcds; ++x) {
       unsigned count;
       if (ps.interleave)   // items x, x + 8, ...
         count = total > x ? (total - x + kXcds - 1) / kXcds : 0;
@@ -128,7 +133,7 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
     };
     const unsigned n_items = (unsigned)n_mtiles * (unsigned)n_ntiles;
     const unsigned per_xcd = (n_items + kXcds - 1) / kXcds;
-    for (unsigned w = threadIdx.x; w < n_items; w += blockDim.x) {
+    for (unsigned w = part * blockDim.x + threadIdx.x; w < n_items; w += n_parts * blockDim.x) {
       const int i = (int)(w % (unsigned)n_mtiles), nt = (int)(w / (unsigned)n_mtiles);
       const int g = group_of_tile(i);
       const int mi = i - s_start[s][g];

@@ -185,6 +185,16 @@ def test_dispatch_parity(T, E, k, p_local):
     _check_dispatch(desc, idx, mask, 64, 2)
 
 
+def test_dispatch_more_assignments_than_256_chunks():
+    """Above 256 x 2048 assignments a workgroup places several chunks in turn."""
+    T, E, k = 150001, 40, 4
+    rng = np.random.default_rng(9)
+    logits = rng.standard_normal((T, E)) - 0.7 * np.log(np.arange(1, E + 1))
+    idx = np.argsort(-logits, axis=1)[:, :k].astype(np.int32)
+    mask = (rng.random(E) < 0.5).astype(np.uint8)
+    _check_dispatch(P.make_desc(64, 64, E, k, 0, "bf16", 0), idx, mask, 64, 2)
+
+
 def test_dispatch_zero_tokens():
     desc = P.make_desc(64, 64, 8, 2, 0, "bf16", 0)
     ws = P.alloc_workspace(desc, 0)
