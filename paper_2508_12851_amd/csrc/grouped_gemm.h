@@ -71,6 +71,18 @@ struct GemmArgs {
 
 constexpr int kGemmThreads = 256;
 
+// Epilogue strips: 32 rows x 64 bf16 columns per wavefront at a row pitch of 144 bytes
+// (16-byte aligned rows whose starts fall into different banks).  Used by the plain GEMM when a
+// wavefront's output is at least 64 bf16 columns wide (the gated GEMM, whose epilogue is
+// dominated by the SiLU arithmetic, ran 5-10 % slower with it).
+constexpr int kStripPitch = 144;
+constexpr int kStripBytes = 32 * kStripPitch;
+template <int WN, bool GATED, bool SPLITK> constexpr bool staged_store() {
+  return !SPLITK && !GATED && (WN / 32) % 2 == 0;
+}
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 // Schedule entries and pointer tables are written before the kernel starts and
 // never during it; reading them through the constant address space lets the
 // compiler use scalar loads, which the vector-memory counter does not see.
@@ -121,6 +133,10 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   constexpr int KK = BK / 16;                 // MFMA k-steps per stage
   static_assert(STAGES >= 3, "ring needs a free stage to refill during an iteration");
   static_assert((STAGES - 1) * LPS <= 63, "vmcnt is a 6-bit counter");
+
+  // wide bf16 output tiles are stored through LDS strips (see the epilogue)
+  constexpr bool kStagedStore = staged_store<WN, GATED, SPLITK>();
+  constexpr int kStripBase = STAGES * kStageBytes + (GATED ? 4096 : 0);
 
   extern __shared__ __align__(16) uint8_t smem[];
 
@@ -365,8 +381,66 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   // The weight rows are the MFMA's first operand, so accumulator register v of
   // lane (r32, q) is output row (activation row) r32 of subtile i and output
   // column 8 (v / 4) + 4 q + v % 4 of subtile j: four consecutive columns per
-  // register quad, written as one 8-byte (bf16) or 16-byte (fp32 partial) store.
+  // register quad, i.e. one 8-byte (bf16) or 16-byte (fp32 partial) piece.
+  //
+  // Stored straight from there, an instruction writes 16 bytes to each of 32 rows, and the
+  // write path then takes a fifth of a short-contraction item (12.6k clocks against 54k of
+  // k-loop for the 1408-long down projection).  Wide bf16 tiles therefore pass every strip
+  // of 32 rows x 64 columns through a 4.5 KiB LDS buffer of the wavefront's own (row pitch
+  // 144 bytes) and store it with 16 bytes per lane, 8 lanes per row: whole 128-byte lines.
+  // The LDS instructions come from assembly: for LDS accesses it sees, the compiler would
+  // first wait for every direct-to-LDS load in flight (the next item's operands).  A
+  // wavefront's LDS instructions execute in order, so the read-back needs no wait after the
+  // writes, nor the next strip's writes after the read-back.
+  auto epilogue_staged = [&](const Ctx& cx) {
+    constexpr int NO = GATED ? NJ / 2 : NJ;                 // output column subtiles of 32
+    const uint32_t strip = (uint32_t)(uintptr_t)(lds_ptr_t)(smem + kStripBase) + wave * kStripBytes;
+    const uint32_t wr = strip + r32 * kStripPitch + q * 8;  // + 2 (32 jl + 8 vg)
+    const int rd_row = lane >> 3, rd_chunk = lane & 7;       // + 8 t rows
+    const uint32_t rd = strip + rd_row * kStripPitch + rd_chunk * 16;
+    const int col0 = (GATED ? cx.nt * (BN / 2) + wn * (WN / 2) : cx.nt * BN + wn * WN) + rd_chunk * 8;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int row0 = (i * WGM + wm) * 32;
+      if (row0 >= cx.row_count) continue;                    // wavefront-uniform
+#pragma unroll
+      for (int jp = 0; jp < NO / 2; ++jp) {
+#pragma unroll
+        for (int jl = 0; jl < 2; ++jl)
+#pragma unroll
+          for (int vg = 0; vg < 4; ++vg) {
+            const int j = jp * 2 + jl;
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              o[e] = GATED ? (bf16_t)(silu(acc[i][j][vg * 4 + e]) * acc[i][j + NO][vg * 4 + e])
+                           : (bf16_t)acc[i][j][vg * 4 + e];
+            asm volatile("ds_write_b64 %0, %1 offset:%2"
+                         :: "v"(wr), "v"(__builtin_bit_cast(u32x2, o)), "n"((jl * 32 + vg * 8) * 2)
+                         : "memory");
+          }
+        u32x4 v[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v[t]) : "v"(rd), "n"(t * 8 * kStripPitch) : "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(v[t]));   // no use moves above the wait
+        const int col = col0 + jp * 64;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int row = row0 + t * 8 + rd_row;
+          if (row < cx.row_count && col < p.N)
+            *reinterpret_cast<u32x4*>(p.C + (size_t)(cx.row_start + row) * p.N + col) = v[t];
+        }
+      }
+    }
+  };
   auto epilogue = [&](const Ctx& cx) {
+    if constexpr (kStagedStore) {
+      epilogue_staged(cx);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int row = (i * WGM + wm) * 32 + r32;
@@ -483,7 +557,8 @@ template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool
           bool ROTATE = false>
 prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int n_splits = 1,
                          int max_slots = 0) {
-  constexpr int smem = STAGES * (BM + BN) * BK * 2 + (GATED ? 4096 : 0);   // ring + source-row slots
+  constexpr int smem = STAGES * (BM + BN) * BK * 2 + (GATED ? 4096 : 0) +   // ring + source-row slots
+                       (staged_store<BN / WGN, GATED, SPLITK>() ? 4 * kStripBytes : 0);   // + strips
   static_assert(smem <= 160 * 1024, "LDS per workgroup");
   constexpr int kCusPerXcd = 32;
   constexpr int kResident = (160 * 1024) / smem;     // workgroups per CU that fit in LDS
