@@ -394,38 +394,55 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   // writes, nor the next strip's writes after the read-back.
   auto epilogue_staged = [&](const Ctx& cx) {
     constexpr int NO = GATED ? NJ / 2 : NJ;                 // output column subtiles of 32
+    constexpr int kPairs = NO / 2 > 0 ? NO / 2 : 1;         // (instantiated for narrow tiles too, never called)
+    constexpr int kStrips = MI * kPairs;                  // strip s: row subtile s / kPairs, column pair s % kPairs
     const uint32_t strip = (uint32_t)(uintptr_t)(lds_ptr_t)(smem + kStripBase) + wave * kStripBytes;
     const uint32_t wr = strip + r32 * kStripPitch + q * 8;  // + 2 (32 jl + 8 vg)
     const int rd_row = lane >> 3, rd_chunk = lane & 7;       // + 8 t rows
     const uint32_t rd = strip + rd_row * kStripPitch + rd_chunk * 16;
     const int col0 = (GATED ? cx.nt * (BN / 2) + wn * (WN / 2) : cx.nt * BN + wn * WN) + rd_chunk * 8;
+    // the values of a strip as this lane holds them: 2 subtiles x 4 quads of 4 bf16
+    auto strip_values = [&](int st, u32x2 (&o)[8]) {
+      const int i = st / kPairs, jp = st % kPairs;
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+      for (int jl = 0; jl < 2; ++jl)
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+          const int j = jp * 2 + jl;
+          bf16x4 b;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            b[e] = GATED ? (bf16_t)(silu(acc[i][j][vg * 4 + e]) * acc[i][j + NO][vg * 4 + e])
+                         : (bf16_t)acc[i][j][vg * 4 + e];
+          o[jl * 4 + vg] = __builtin_bit_cast(u32x2, b);
+        }
+    };
+    // Strip st + 1 is computed while the writes of strip st are on their way.
+    u32x2 cur[8], nxt[8];
+    strip_values(0, cur);
+#pragma unroll
+    for (int st = 0; st < kStrips; ++st) {
+      const int i = st / kPairs, jp = st % kPairs;
       const int row0 = (i * WGM + wm) * 32;
-      if (row0 >= cx.row_count) continue;                    // wavefront-uniform
+      const bool live = row0 < cx.row_count;                // wavefront-uniform
+      if (live) {
 #pragma unroll
-      for (int jp = 0; jp < NO / 2; ++jp) {
-#pragma unroll
-        for (int jl = 0; jl < 2; ++jl)
-#pragma unroll
-          for (int vg = 0; vg < 4; ++vg) {
-            const int j = jp * 2 + jl;
-            bf16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              o[e] = GATED ? (bf16_t)(silu(acc[i][j][vg * 4 + e]) * acc[i][j + NO][vg * 4 + e])
-                           : (bf16_t)acc[i][j][vg * 4 + e];
-            asm volatile("ds_write_b64 %0, %1 offset:%2"
-                         :: "v"(wr), "v"(__builtin_bit_cast(u32x2, o)), "n"((jl * 32 + vg * 8) * 2)
-                         : "memory");
-          }
-        u32x4 v[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-          asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v[t]) : "v"(rd), "n"(t * 8 * kStripPitch) : "memory");
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(v[t]));   // no use moves above the wait
+        for (int w8 = 0; w8 < 8; ++w8)
+          asm volatile("ds_write_b64 %0, %1 offset:%2"
+                       :: "v"(wr), "v"(cur[w8]), "n"(((w8 / 4) * 32 + (w8 % 4) * 8) * 2) : "memory");
+      }
+      if (st + 1 < kStrips) strip_values(st + 1, nxt);
+      if (live) {
+        // one statement up to the wait: the compiler takes an output for valid as soon as its
+        // statement ends (and may copy it elsewhere right away)
+        u32x4 v0, v1, v2, v3;
+        asm volatile(
+            "ds_read_b128 %0, %4 offset:%5\n\tds_read_b128 %1, %4 offset:%6\n\t"
+            "ds_read_b128 %2, %4 offset:%7\n\tds_read_b128 %3, %4 offset:%8\n\ts_waitcnt lgkmcnt(0)"
+            : "=&v"(v0), "=&v"(v1), "=&v"(v2), "=&v"(v3)
+            : "v"(rd), "n"(0), "n"(8 * kStripPitch), "n"(16 * kStripPitch), "n"(24 * kStripPitch)
+            : "memory");
+        const u32x4 v[4] = {v0, v1, v2, v3};
         const int col = col0 + jp * 64;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -434,6 +451,8 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
             *reinterpret_cast<u32x4*>(p.C + (size_t)(cx.row_start + row) * p.N + col) = v[t];
         }
       }
+#pragma unroll
+      for (int w8 = 0; w8 < 8; ++w8) cur[w8] = nxt[w8];
     }
   };
   auto epilogue = [&](const Ctx& cx) {

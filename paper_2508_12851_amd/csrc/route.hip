@@ -285,6 +285,40 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_kernel(
 // finishing wavefront taking four tokens of one tile.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// N consecutive 1 KiB blocks of LDS, 16 bytes per lane at byte address addr + 1024 b, then
+// the wait for them.  One assembly statement up to the wait: the compiler takes an output for
+// valid as soon as its statement ends (and may copy it elsewhere right away).  From assembly
+// because for LDS reads it sees, the compiler first waits for every direct-to-LDS load in
+// flight, the prefetched slices included.
+template <int N>
+__device__ __forceinline__ void read_blocks(u32x4 (&o)[N], uint32_t addr) {
+  static_assert(N >= 2 && N <= 6, "TMB + NT blocks");
+  if constexpr (N == 2)
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:1024\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(o[0]), "=&v"(o[1]) : "v"(addr) : "memory");
+  else if constexpr (N == 3)
+    asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %3 offset:1024\n\t"
+                 "ds_read_b128 %2, %3 offset:2048\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]) : "v"(addr) : "memory");
+  else if constexpr (N == 4)
+    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:1024\n\t"
+                 "ds_read_b128 %2, %4 offset:2048\n\tds_read_b128 %3, %4 offset:3072\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]) : "v"(addr) : "memory");
+  else if constexpr (N == 5)
+    asm volatile("ds_read_b128 %0, %5\n\tds_read_b128 %1, %5 offset:1024\n\t"
+                 "ds_read_b128 %2, %5 offset:2048\n\tds_read_b128 %3, %5 offset:3072\n\t"
+                 "ds_read_b128 %4, %5 offset:4096\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]), "=&v"(o[4]) : "v"(addr) : "memory");
+  else
+    asm volatile("ds_read_b128 %0, %6\n\tds_read_b128 %1, %6 offset:1024\n\t"
+                 "ds_read_b128 %2, %6 offset:2048\n\tds_read_b128 %3, %6 offset:3072\n\t"
+                 "ds_read_b128 %4, %6 offset:4096\n\tds_read_b128 %5, %6 offset:5120\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]), "=&v"(o[4]), "=&v"(o[5])
+                 : "v"(addr) : "memory");
+}
+
 template <int NT, int TMB>
 struct StagedCfg {
   static constexpr int kBlocks = TMB + NT;                       // 1 KiB blocks per slice
@@ -391,21 +425,9 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_staged_kernel(
   int buf = 0;
   for (int i = 0; i < n_mine; ++i) {
     wait_vmcnt<(kDepth - 1) * kBlocks>();                 // slice i has landed
-    // The LDS reads are issued from assembly: for reads the compiler sees, it waits until
-    // every direct-to-LDS load in flight has landed, the prefetched slices included.
     const uint32_t sb = lds_base + buf * (kBlocks * 1024);
-    u32x4 xa[TMB], wb[NT];
-#pragma unroll
-    for (int b = 0; b < TMB; ++b)
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(xa[b]) : "v"(sb), "n"(b * 1024));
-#pragma unroll
-    for (int n = 0; n < NT; ++n)
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(wb[n]) : "v"(sb), "n"((TMB + n) * 1024));
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");    // read before the refill may overwrite it
-#pragma unroll
-    for (int b = 0; b < TMB; ++b) asm volatile("" : "+v"(xa[b]));   // no use moves above the wait
-#pragma unroll
-    for (int n = 0; n < NT; ++n) asm volatile("" : "+v"(wb[n]));
+    u32x4 blk[kBlocks];
+    read_blocks(blk, sb);                                  // waits: read before the refill may overwrite it
     issue(slice_of(i + kDepth), buf);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -415,10 +437,10 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void route_staged_kernel(
       };
       double a[TMB];
 #pragma unroll
-      for (int b = 0; b < TMB; ++b) a[b] = element(xa[b]);
+      for (int b = 0; b < TMB; ++b) a[b] = element(blk[b]);
 #pragma unroll
       for (int n = 0; n < NT; ++n) {
-        const double bw = element(wb[n]);
+        const double bw = element(blk[TMB + n]);
 #pragma unroll
         for (int b = 0; b < TMB; ++b)
           acc[b][n] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[b], bw, acc[b][n], 0, 0, 0);
