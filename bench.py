@@ -106,9 +106,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--trace-all", action="store_true", help="also time every stage (stderr)")
-    ap.add_argument("--weight-layout", choices=("row_major", "blocked64"), default="row_major",
-                    help="expert weight layout in HBM; blocked64 is packed once, outside the timed "
-                         "region, as a server does when it loads or receives an expert")
+    ap.add_argument("--weight-layout", choices=("row_major", "tiled"), default="tiled",
+                    help="expert weight layout in HBM; tiled (16 x 32 tiles) is packed once, outside the "
+                         "timed region, as a server does when it loads or receives an expert")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the measured MFMA / HBM ceilings of this GPU")
     args = ap.parse_args()
@@ -139,7 +139,7 @@ def main():
 
     desc = P.make_desc(cfg.H, cfg.F, cfg.E, cfg.k, cfg.S, cfg.dtype, cfg.bias_group_tokens,
                        weight_layout=args.weight_layout)
-    wdev = (lambda a: P.prism_pack_weights(dev(a))) if args.weight_layout == "blocked64" else dev
+    wdev = (lambda a: P.prism_pack_weights(dev(a))) if args.weight_layout == "tiled" else dev
     experts = [tuple(wdev(w) for w in inp.expert(e)) if inp.mask[e] else None for e in range(cfg.E)]
     shared = [tuple(wdev(w) for w in inp.shared(s)) for s in range(cfg.S)]
     tables = [P.WeightTable(experts, shared)]
@@ -234,7 +234,9 @@ def main():
                    "experts": cfg.E, "top_k": cfg.k, "shared_experts": cfg.S,
                    "local_experts": int(inp.mask.sum()), "n_local": n_local, "n_remote": n_remote,
                    "remote_bytes_each_way": int(out.remote_bytes[0]),
-                   "weight_copies_rotated": len(tables), "weight_layout": args.weight_layout},
+                   "weight_copies_rotated": len(tables),
+                   "weight_layout": args.weight_layout + (" (packed once at load, not timed)"
+                                                          if args.weight_layout == "tiled" else "")},
         "roofline": roofline,
         "layer_tflops": layer_flop / (ms_per_step * 1e-3) / 1e12,
         "step_ms_median": step_ms[len(step_ms) // 2], "step_ms_min": step_ms[0],

@@ -85,13 +85,14 @@ typedef enum {
 } prism_gate_mode;
 
 /* Memory layout of every expert weight matrix [rows, cols] (w_gate, w_up: [F,H]; w_down: [H,F]).
- * PRISM_WEIGHTS_BLOCKED64 (bf16 layers only): 64 x 64 element blocks of 8 KiB, blocks stored
- * row-block major, rows of a block 128 bytes apart; element (r, c) lies at byte
- *   ((r / 64) * (cols / 64) + c / 64) * 8192 + (r % 64) * 128 + (c % 64) * 2.
- * A matrix is brought into it once, when the expert is loaded, with prism_pack_weights; the
- * kernels then fetch contiguous 8 KiB blocks instead of 64- or 128-byte pieces of rows that lie
- * 8 - 28 KiB apart, which the memory serves a few percent faster.  Results are bit-identical. */
-typedef enum { PRISM_WEIGHTS_ROW_MAJOR = 0, PRISM_WEIGHTS_BLOCKED64 = 1 } prism_weight_layout;
+ * PRISM_WEIGHTS_TILED (bf16 layers only): tiles of 16 rows x 32 columns, 1 KiB each, stored
+ * row-tile major, the rows of a tile 64 bytes apart; element (r, c) lies at byte
+ *   ((r / 16) * (cols / 32) + c / 32) * 1024 + (r % 16) * 64 + (c % 32) * 2.
+ * A matrix is brought into it once, when the expert is loaded, with prism_pack_weights.  The
+ * prefill kernels consume 32 columns of a weight row at a time: from a row-major matrix that is
+ * one half of a 128-byte cache line per row, and the L2 delivers the whole line both times;
+ * from a tile, every line fetched is used completely.  Results are bit-identical. */
+typedef enum { PRISM_WEIGHTS_ROW_MAJOR = 0, PRISM_WEIGHTS_TILED = 1 } prism_weight_layout;
 
 /* Layer description: plain data in HOST memory, passed by const pointer. */
 typedef struct {
@@ -272,11 +273,11 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                                     void* stream, void* const* stage_events);
 
 /*
- * Re-lays a row-major bf16 matrix [rows, cols] into PRISM_WEIGHTS_BLOCKED64 (see
- * prism_weight_layout).  rows and cols must be multiples of 64; src and dst are device
+ * Re-lays a row-major bf16 matrix [rows, cols] into PRISM_WEIGHTS_TILED (see
+ * prism_weight_layout).  rows must be a multiple of 16, cols of 32; src and dst are device
  * buffers of rows * cols * 2 bytes, 16-byte aligned, and must not overlap.  Enqueues one
  * kernel on `stream`.  Errors: PRISM_ERR_INVALID_ARG (NULL, sizes < 1, misaligned),
- * PRISM_ERR_UNSUPPORTED (sizes not multiples of 64, or the matrix is 4 GiB or more).
+ * PRISM_ERR_UNSUPPORTED (rows not a multiple of 16, cols not of 32, or the matrix is 4 GiB or more).
  */
 prism_status prism_pack_weights(const void* src, int32_t rows, int32_t cols, void* dst, void* stream);
 

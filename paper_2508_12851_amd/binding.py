@@ -23,7 +23,7 @@ SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism
            "prism_combine_remote", "prism_debug_check_weights", "prism_pack_weights")
 STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
 GATE_MODES = {"renormalized": 0, "softmax_all": 1}
-WEIGHT_LAYOUTS = {"row_major": 0, "blocked64": 1}
+WEIGHT_LAYOUTS = {"row_major": 0, "tiled": 1}
 
 
 class PrismError(RuntimeError):
@@ -323,7 +323,7 @@ def prism_debug_check_weights(desc: LayerDesc, weights: WeightTable, local_mask)
 
 
 def prism_pack_weights(w, stream=None) -> torch.Tensor:
-    """Row-major bf16 weight matrix -> the 64 x 64 blocked layout (a new tensor of the same shape)."""
+    """Row-major bf16 weight matrix -> the layout of 16 x 32 tiles (a new tensor of the same shape)."""
     rows, cols = w.shape
     packed = torch.empty_like(w)
     _check(load_library().prism_pack_weights(_ptr(w), rows, cols, _ptr(packed), _stream(stream)),

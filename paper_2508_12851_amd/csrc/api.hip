@@ -11,9 +11,9 @@ prism_status validate_desc(const prism_layer_desc* d, int32_t T, bool need_ffn_s
   PRISM_RETURN_IF(d->bias_group_tokens < 0, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(d->gate_mode != PRISM_GATES_RENORMALIZED && d->gate_mode != PRISM_GATES_SOFTMAX_ALL,
                   PRISM_ERR_INVALID_ARG);
-  PRISM_RETURN_IF(d->weight_layout != PRISM_WEIGHTS_ROW_MAJOR && d->weight_layout != PRISM_WEIGHTS_BLOCKED64,
+  PRISM_RETURN_IF(d->weight_layout != PRISM_WEIGHTS_ROW_MAJOR && d->weight_layout != PRISM_WEIGHTS_TILED,
                   PRISM_ERR_INVALID_ARG);
-  PRISM_RETURN_IF(d->weight_layout == PRISM_WEIGHTS_BLOCKED64 && d->dtype != PRISM_BF16, PRISM_ERR_UNSUPPORTED);
+  PRISM_RETURN_IF(d->weight_layout == PRISM_WEIGHTS_TILED && d->dtype != PRISM_BF16, PRISM_ERR_UNSUPPORTED);
   PRISM_RETURN_IF(d->dtype != PRISM_F32 && d->dtype != PRISM_BF16, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(d->n_experts > PRISM_MAX_EXPERTS || d->top_k > PRISM_MAX_TOPK ||
                       d->n_shared > PRISM_MAX_SHARED,
@@ -162,7 +162,7 @@ prism_status prism_combine_remote(const prism_layer_desc* desc, const void* y_re
 prism_status prism_pack_weights(const void* src, int32_t rows, int32_t cols, void* dst, void* stream) {
   PRISM_RETURN_IF(src == nullptr || dst == nullptr || rows < 1 || cols < 1, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF((((uintptr_t)src | (uintptr_t)dst) & 15u) != 0, PRISM_ERR_INVALID_ARG);
-  PRISM_RETURN_IF(rows % 64 != 0 || cols % 64 != 0, PRISM_ERR_UNSUPPORTED);
+  PRISM_RETURN_IF(rows % 16 != 0 || cols % 32 != 0, PRISM_ERR_UNSUPPORTED);
   PRISM_RETURN_IF((size_t)rows * cols * 2 >= 0xFFFF0000ull, PRISM_ERR_UNSUPPORTED);
   return launch_pack_weights(src, rows, cols, dst, (hipStream_t)stream);
 }

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const TIO* __restrict__ 
 }
 
 // One 16-byte chunk (8 bf16) per thread from the row-major matrix to its place in the
-// 64 x 64 blocked layout.
+// layout of 16 x 32 tiles.
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint4* __restrict__ src, int rows,
                                                            int cols, uint4* __restrict__ dst) {
   const int chunks_per_row = cols / 8;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint4* __restri
   if (gid >= (long long)rows * chunks_per_row) return;
   const unsigned r = (unsigned)(gid / chunks_per_row);
   const unsigned c = (unsigned)(gid - (long long)r * chunks_per_row) * 8;   // first column
-  const size_t byte = ((size_t)(r >> 6) * (cols >> 6) + (c >> 6)) * 8192 + (r & 63u) * 128 + (c & 63u) * 2;
+  const size_t byte = ((size_t)(r >> 4) * (cols >> 5) + (c >> 5)) * 1024 + (r & 15u) * 64 + (c & 31u) * 2;
   dst[byte / 16] = src[gid];
 }
 

@@ -172,7 +172,7 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   g1.a_bytes = (uint32_t)((size_t)T * d.hidden * 2);
   g1.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g1.K = d.hidden; g1.N = d.ffn; g1.top_k = d.top_k; g1.E = d.n_experts;
-  g1.b_blocked = d.weight_layout == PRISM_WEIGHTS_BLOCKED64;
+  g1.b_tiled = d.weight_layout == PRISM_WEIGHTS_TILED;
   trace(stage_events, PRISM_STAGE_FFN_UP, 0, st);
   PRISM_TRY((gg::launch_gemm<C1::BM, C1::BN, 2, 2, C1::BK, C1::STAGES, true, false, kRotate>(
       g1, gg::sched_capacity(d, T, C1::BM, nt1), st)));
@@ -187,7 +187,7 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   g2.a_bytes = (uint32_t)((size_t)rows * d.ffn * 2);
   g2.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g2.K = d.ffn; g2.N = d.hidden; g2.top_k = d.top_k; g2.E = d.n_experts;
-  g2.b_blocked = d.weight_layout == PRISM_WEIGHTS_BLOCKED64;
+  g2.b_tiled = d.weight_layout == PRISM_WEIGHTS_TILED;
   // every contraction slice must be at least as long as the k-tile ring
   int n_splits = 1;
   if (SPLIT_DOWN) {
@@ -255,6 +255,11 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
     // different column ranges of the weight rows, whose power-of-two pitch would
     // otherwise send them all to the same few memory channels.
     // (ffn_schedule_shapes() below states the tile shapes of all variants)
+    // Tiled weights: 32-wide k-tiles, so that one load instruction takes one whole 1 KiB
+    // tile (with 64-wide k-tiles it would take halves of two), and twice the stages.
+    if (d.weight_layout == PRISM_WEIGHTS_TILED && d.hidden >= 256 && d.ffn >= 1024)
+      return run_bf16_ffn<TileCfg<64, 128, 32, 8>, TileCfg<64, 128, 32, 8>, true>(
+          d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
     if (d.hidden >= 192 && d.ffn >= 192)
       return run_bf16_ffn<TileCfg<64, 128, 64, 4>, TileCfg<64, 128, 64, 4>, true>(
           d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);

@@ -66,7 +66,7 @@ struct GemmArgs {
   int N;                    // output columns (F for GEMM1, H for GEMM2)
   int top_k;
   int E;
-  int b_blocked;            // weights in the 64 x 64 blocked layout (prism.h) instead of row-major
+  int b_tiled;              // weights in 16 x 32 tiles (prism.h) instead of row-major
 };
 
 constexpr int kGemmThreads = 256;
@@ -225,11 +225,15 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
                                                it.row_start * 4, 0, 0);
     return r;
   };
-  // Byte offset of weight row n at contraction element 0 (the k offset is added per k-tile):
-  // row-major, or 64 x 64 blocks of 8 KiB laid out row-block major.
+  // Byte offset of this lane's 16-byte chunk c of weight row n in k-tile 0 (the k-tile offset
+  // is added per load): row-major, or tiles of 16 rows x 32 columns (1 KiB, rows 64 bytes
+  // apart) laid out row-tile major -- a 64-wide k-tile spans two neighbouring tiles.
+  auto tiled_offset = [&](uint32_t n, uint32_t cols) {
+    return (n >> 4) * (cols >> 5) * 1024u + (n & 15u) * 64u + (uint32_t)(c >> 2) * 1024u +
+           (uint32_t)(c & 3) * 16u;
+  };
   auto weight_row_offset = [&](uint32_t n) {
-    return p.b_blocked ? (n >> 6) * ((uint32_t)p.K >> 6) * 8192u + (n & 63u) * 128u
-                       : n * (uint32_t)p.K * 2u;
+    return p.b_tiled ? tiled_offset(n, (uint32_t)p.K) : n * (uint32_t)p.K * 2u + (uint32_t)c * 16u;
   };
   auto make_ctx = [&](const Item& it, const Raw& raw) {
     Ctx cx;
@@ -258,10 +262,10 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
         // tile rows [w WN, w WN + WN/2) are gate rows, the next WN/2 the up rows of the same f
         const int w = g0 / WN, within = g0 % WN;
         const int f = min(it.nt * (BN / 2) + w * (WN / 2) + (within % (WN / 2)) + sub, p.N - 1);
-        cx.b_voff[i] = weight_row_offset((uint32_t)f) + c * 16;
+        cx.b_voff[i] = weight_row_offset((uint32_t)f);
       } else {
         const int n = min(it.nt * BN + g0 + sub, p.N - 1);
-        cx.b_voff[i] = weight_row_offset((uint32_t)n) + c * 16;
+        cx.b_voff[i] = weight_row_offset((uint32_t)n);
       }
     }
     return cx;
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     }
     const int kel = (kt_first + kt_mem) * BK;                 // first contraction element
     const int koff = kel * 2;
-    const int koff_b = p.b_blocked ? (kel >> 6) * 8192 + (kel & 63) * 2 : koff;
+    const int koff_b = p.b_tiled ? (kel >> 5) * 1024 : koff;   // kel is a multiple of 32
     const __amdgpu_buffer_rsrc_t b0_rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)cx.b0, 0, (int)p.b_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t b1_rsrc =

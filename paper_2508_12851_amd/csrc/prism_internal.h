@@ -176,7 +176,7 @@ prism_status launch_combine(const prism_layer_desc& d, const void* y, const int3
                             const float* topk_gate, int T, void* out, hipStream_t st,
                             const float* part = nullptr, int n_splits = 0, bool add_to_out = false);
 
-// Row-major bf16 [rows, cols] -> 64 x 64 blocked layout (rows, cols multiples of 64).
+// Row-major bf16 [rows, cols] -> 16 x 32 tiles (rows a multiple of 16, cols of 32).
 prism_status launch_pack_weights(const void* src, int rows, int cols, void* dst, hipStream_t st);
 
 // packed[r] = x[src[r] / k] for the rows r < offsets[E] of an assignment list.

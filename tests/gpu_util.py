@@ -22,12 +22,12 @@ def desc_of(cfg, gate_mode="renormalized", weight_layout="row_major"):
                        weight_layout)
 
 
-def weight_table(inp, mask=None, all_experts=False, blocked=False):
-    """Upload hosted experts (None for the others) and the shared experts; blocked: re-laid
-    into the 64 x 64 blocked layout by the library's own pack kernel."""
+def weight_table(inp, mask=None, all_experts=False, tiled=False):
+    """Upload hosted experts (None for the others) and the shared experts; tiled: re-laid
+    into 16 x 32 tiles by the library's own pack kernel."""
     c = inp.cfg
     mask = inp.mask if mask is None else mask
-    up = (lambda w: P.prism_pack_weights(to_dev(w))) if blocked else to_dev
+    up = (lambda w: P.prism_pack_weights(to_dev(w))) if tiled else to_dev
     experts = []
     for e in range(c.E):
         if all_experts or mask[e]:

@@ -83,17 +83,17 @@ def test_unknown_gate_mode_is_rejected():
 def test_weight_layout_validation():
     lib = P.load_library()
     n = ctypes.c_size_t(0)
-    d = P.make_desc(128, 128, 8, 2, 0, "bf16", weight_layout="blocked64")
+    d = P.make_desc(128, 128, 8, 2, 0, "bf16", weight_layout="tiled")
     assert lib.prism_workspace_bytes(ctypes.byref(d), 16, ctypes.byref(n)) == 0
     d.weight_layout = 5
     assert lib.prism_workspace_bytes(ctypes.byref(d), 16, ctypes.byref(n)) == 1
-    d = P.make_desc(128, 128, 8, 2, 0, "f32", weight_layout="blocked64")       # bf16 layers only
+    d = P.make_desc(128, 128, 8, 2, 0, "f32", weight_layout="tiled")       # bf16 layers only
     assert lib.prism_workspace_bytes(ctypes.byref(d), 16, ctypes.byref(n)) == 2
-    # prism_pack_weights: NULL, misaligned and non-multiples of 64 are refused before any launch
+    # prism_pack_weights: NULL, misaligned, rows not in 16s and columns not in 32s are refused before any launch
     assert lib.prism_pack_weights(None, 64, 64, None, None) == 1
     assert lib.prism_pack_weights(ctypes.c_void_p(0x1000), 0, 64, ctypes.c_void_p(0x2000), None) == 1
     assert lib.prism_pack_weights(ctypes.c_void_p(0x1008), 64, 64, ctypes.c_void_p(0x2000), None) == 1
-    assert lib.prism_pack_weights(ctypes.c_void_p(0x1000), 96, 64, ctypes.c_void_p(0x2000), None) == 2
+    assert lib.prism_pack_weights(ctypes.c_void_p(0x1000), 72, 64, ctypes.c_void_p(0x2000), None) == 2
     assert lib.prism_pack_weights(ctypes.c_void_p(0x1000), 64, 100, ctypes.c_void_p(0x2000), None) == 2
 
 
