@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--weight-layout", choices=("row_major", "tiled"), default="tiled",
                     help="expert weight layout in HBM; tiled (16 x 32 tiles) is packed once, outside the "
                          "timed region, as a server does when it loads or receives an expert")
+    ap.add_argument("--mask", choices=("top", "random"), default="top",
+                    help="hosted experts: the most popular ones (what the first loop of Alg. 2 hosts) or a "
+                         "seeded uniformly random subset of the same size (the uniform baseline of Sec. IV)")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the measured MFMA / HBM ceilings of this GPU")
     args = ap.parse_args()
@@ -118,12 +121,14 @@ def main():
 
     import torch
     import paper_2508_12851_amd as P
-    from prism_inputs import CONFIGS, make_inputs
+    from prism_inputs import CONFIGS, make_config, make_inputs
 
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(1)
     cfg = CONFIGS[args.config]
+    if args.mask == "random":
+        cfg = make_config(args.config, mask_kind="random")
     decode = cfg.T <= 64
     steps = args.steps if args.steps is not None else (200 if decode else 30)
     warmup = args.warmup if args.warmup is not None else (20 if decode else 5)
@@ -200,6 +205,13 @@ def main():
                                                for i in range(steps)]))
     n_local, n_remote = out.n_local_remote.cpu().tolist()
     counts = out.counts.cpu().numpy()
+    # tokens with at least one remote slot: what a sender that ships a token once per peer, not
+    # once per assignment, would at least have to send (the byte counts are per assignment)
+    remote_tokens = int((inp.mask[out.topk_idx.cpu().numpy()] == 0).any(axis=1).sum())
+    share = np.sort(counts.astype(np.float64) / max(1, counts.sum()))[::-1]
+    zipf = np.arange(1, cfg.E + 1, dtype=np.float64) ** -cfg.zipf_s
+    log(f"[bench] realised expert shares (sorted) {np.round(share[:8], 3).tolist()} ... against Zipf(s={cfg.zipf_s}) "
+        f"{np.round((zipf / zipf.sum())[:8], 3).tolist()}; tokens with a remote slot: {remote_tokens} of {cfg.T}")
     rows = n_local + cfg.S * cfg.T
     es = cfg.es
     dom_ms = stage_ms["ffn_up"]
@@ -234,6 +246,7 @@ def main():
                    "experts": cfg.E, "top_k": cfg.k, "shared_experts": cfg.S,
                    "local_experts": int(inp.mask.sum()), "n_local": n_local, "n_remote": n_remote,
                    "remote_bytes_each_way": int(out.remote_bytes[0]),
+                   "tokens_with_a_remote_slot": remote_tokens, "mask": args.mask,
                    "weight_copies_rotated": len(tables),
                    "weight_layout": args.weight_layout + (" (packed once at load, not timed)"
                                                           if args.weight_layout == "tiled" else "")},
