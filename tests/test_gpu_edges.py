@@ -113,3 +113,37 @@ def test_debug_check_finds_a_hosted_expert_without_weights():
     with pytest.raises(P.PrismError, match=f"expert {hosted}"):
         P.prism_debug_check_weights(desc, weight_table(inp, holes), mask)  # ... but the mask hosts it
     P.prism_debug_check_weights(desc, weight_table(inp, holes), to_dev(holes))
+
+
+def test_prefill_layer_graph_replay_equals_eager():
+    """A prefill layer (staged router, two-launch dispatch with the schedule workgroups, both GEMMs,
+    combine) captured in a graph and replayed with the workspace and outputs poisoned in between
+    gives the eager result every time: the library allocates nothing and needs no memset node."""
+    cfg = make_config("cfg4_finegrained", T=2500, H=128, F=192, bias_group_tokens=512)
+    inp = make_inputs(cfg)
+    desc = desc_of(cfg)
+    ws = P.alloc_workspace(desc, cfg.T)
+    out = P.alloc_layer_out(desc, cfg.T)
+    wt = weight_table(inp)
+    x, wr, b, m = to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias), to_dev(inp.mask)
+    P.prism_moe_layer(desc, x, wr, b, wt, m, ws, out)
+    torch.cuda.synchronize()
+    eager = {k: getattr(out, k).clone() for k in ("out", "topk_idx", "counts", "remote_src", "remote_bytes")}
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            P.prism_moe_layer(desc, x, wr, b, wt, m, ws, out, stream=side)
+    torch.cuda.synchronize()
+    for i in range(3):
+        out.out.fill_(float("nan"))
+        out.counts.fill_(-1)
+        out.remote_src.fill_(-7)
+        ws.fill_(0x7F)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        nr = int(out.n_local_remote[1])
+        assert torch.equal(out.out, eager["out"]) and torch.equal(out.topk_idx, eager["topk_idx"]), i
+        assert torch.equal(out.counts, eager["counts"]) and torch.equal(out.remote_bytes, eager["remote_bytes"])
+        assert torch.equal(out.remote_src[:nr], eager["remote_src"][:nr])
