@@ -48,3 +48,17 @@ def test_bench_prints_one_json_line_with_the_contract_keys(config, bound, unit):
     assert "sample" in cb and "8" in cb["sample"]
     assert set(d["measured_ceilings"]) == {"mfma_bf16_constant_operands_tflops",
                                            "mfma_bf16_random_operands_tflops", "hbm_read_gbs"}
+
+
+@pytest.mark.gpu
+def test_bench_options_show_up_in_the_config_it_reports():
+    r = subprocess.run([sys.executable, BENCH, "--config", "cfg3_mixtral_decode", "--steps", "3", "--warmup", "1",
+                        "--mask", "random", "--weight-layout", "row_major", "--no-cpu-baseline", "--no-ceilings"],
+                       capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads(r.stdout.strip())
+    c = d["config"]
+    assert c["mask"] == "random" and c["weight_layout"] == "row_major" and c["local_experts"] == 5
+    assert 0 <= c["tokens_with_a_remote_slot"] <= c["tokens"]
+    assert c["n_local"] + c["n_remote"] == c["tokens"] * c["top_k"]
+    assert "cpu_baseline" not in d and "measured_ceilings" not in d
