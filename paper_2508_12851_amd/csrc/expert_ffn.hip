@@ -5,15 +5,15 @@
 //   GEMM2  y[r, n] = h[r] . W_down^e[n]
 //
 // Both are "NT" contractions (activation rows and weight rows are contiguous
-// along the contraction index), grouped by expert: a device-built tile table
-// lists (expert, first row, row count) for every row tile, so the host never
-// needs the routing-dependent segment sizes.
+// along the contraction index), grouped by expert: device-built work schedules
+// list the (row tile, column tile) items of every hosted expert, so the host
+// never needs the routing-dependent segment sizes.
 //
-// bf16 path: v_mfma_f32_32x32x16_bf16, 4 wavefronts per workgroup, operand
-// tiles of 64 contraction elements staged in LDS (double buffered, 16-byte
-// chunks XOR-swizzled by row so the 16-byte MFMA operand reads spread over all
-// banks).  GEMM1 loads the gate rows and the up rows of the same f range into
-// one tile, so silu(gate)*up is a register epilogue and only h is written.
+// bf16 path: the persistent grouped GEMM of grouped_gemm.h
+// (v_mfma_f32_32x32x16_bf16, 4 wavefronts per workgroup, operand k-tiles in an
+// LDS ring filled by direct-to-LDS loads), in the tile shapes chosen at the end
+// of this file.  GEMM1 loads the gate rows and the up rows of the same f range
+// into one tile, so silu(gate)*up is a register epilogue and only h is written.
 // Activation rows of GEMM1 are gathered through local_src (no permuted copy of
 // x is materialised).
 #include "grouped_gemm.h"
