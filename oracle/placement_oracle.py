@@ -59,7 +59,9 @@ notes of the repository):
 
 Pins (tests/test_placement_pins.py): entropy closed forms (uniform -> log2 E,
 one-hot -> 0, two equal halves -> 1 bit, scale invariance) and the chain rule
-against scipy; Alg. 1 on hand-worked examples and its conservation laws (a
+against scipy; Alg. 1 on hand-worked examples (visiting order, which layer gives,
+ties, a fresh choice per server, layers at exactly E, servers without the donor
+layer) and its conservation laws (a
 server's total over layers never changes in step 2; totals reach E when the
 memory suffices); Alg. 2's top-N property, set sizes, coverage, brute-force
 optimality of the unrepaired choice for Eq. 2, and hand-worked repairs; Eq. 2

@@ -44,7 +44,7 @@ zero-router / duplicated-row / huge-bias closed forms, torch-CPU softmax+topk
 on tie-free inputs, histogram and partition invariants, the dense reference
 MoE written as a T x E gate matrix, mask-complement additivity, linearity in
 W_down, the E=1,k=1 case against torch's SwiGLU MLP, token-permutation
-equivariance.  Nothing here is "parity unpinned" except absolute output
+equivariance, hand values for the rounding of the remote combine.  Nothing here is "parity unpinned" except absolute output
 values at the large configs, which have no source other than this file.
 """
 from __future__ import annotations

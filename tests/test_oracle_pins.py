@@ -437,6 +437,18 @@ def test_remote_call_completes_the_layer():
     assert np.array_equal(same, full.out)
 
 
+def test_combine_remote_rounds_once_to_the_layer_dtype():
+    """Hand values: 1 + g*y with one bf16 rounding (bf16 spacing just above 1 is 2^-7)."""
+    gate = np.array([[0.5, 0.5]], np.float32)
+    src = np.array([1], np.int64)                       # slot 1 of token 0 is the remote one
+    one = np.ones((1, 4))
+    y = np.array([[2.0 ** -8, 3 * 2.0 ** -8, 2.0 ** -7, 5 * 2.0 ** -8]])   # added: half of these
+    got = O.combine_remote(one, y, src, gate, "bf16")
+    # 1 + 2^-9 -> 1;  1 + 3*2^-9 -> 1 + 2^-7;  1 + 2^-8 is a tie -> even (1);  1 + 5*2^-9 -> 1 + 2^-7
+    assert np.array_equal(got, np.array([[1.0, 1.0 + 2.0 ** -7, 1.0, 1.0 + 2.0 ** -7]], np.float32))
+    assert np.array_equal(O.combine_remote(one, y, src, gate, "f32"), (1.0 + 0.5 * y).astype(np.float32))
+
+
 # ---------------------------------------------------------------------------
 # gates without renormalisation: the picked entries of the softmax over all experts
 # ---------------------------------------------------------------------------

@@ -70,6 +70,35 @@ def test_random_small_instances_with_many_ties(seed):
     assert np.array_equal(p_got, p_ref) and c_got == c_ref
 
 
+HAND_ALLOC = [
+    # (v, memory, E, expected N_{n,l}, feasible) -- the hand-worked cases of the oracle's pins
+    ([[1.0, 1.0], [1.0, 3.0]], [4.0, 4.0], 4, [[3, 1], [1, 3]], True),
+    ([[1.0, 3.0, 4.0], [1.0, 3.0, 4.0]], [8.0, 8.0], 4, [[2, 3, 3], [2, 3, 3]], True),
+    ([[2.0, 7.0, 7.0], [2.0, 7.0, 7.0]], [8.0, 8.0], 4, [[2, 2, 3], [2, 3, 2]], True),
+    ([[1.0, 2.0, 1.0]], [4.0], 2, [[1, 2, 1]], False),
+    ([[0.0, 1.0, 0.0], [1.0, 0.0, 7.0], [0.0, 0.0, 1.0]], [8.0, 8.0, 4.0], 3,
+     [[0, 3, 0], [2, 0, 2], [1, 0, 2]], True),
+]
+
+
+@pytest.mark.parametrize("case", range(len(HAND_ALLOC)))
+def test_native_count_allocation_on_hand_worked_cases(case):
+    v, mem, E, want, feasible = HAND_ALLOC[case]
+    cnt, ok = NP.expert_count_allocation(np.array(v), mem, 1.0, E)
+    assert cnt.tolist() == want and ok == feasible
+
+
+def test_native_assignment_on_hand_worked_cases():
+    place, _ = NP.expert_assignment(np.array([[[5, 5, 1]]], np.int64), np.array([[1]]))
+    assert place[0, 0].tolist() == [1, 0, 0]
+    f = np.array([[[9, 8, 1, 0]], [[9, 8, 7, 1]], [[1, 2, 9, 3]]], np.int64)
+    place, covered = NP.expert_assignment(f, np.array([[2], [3], [1]]))
+    assert covered and place[:, 0].tolist() == [[1, 1, 0, 0], [1, 1, 1, 0], [0, 0, 0, 1]]
+    f = np.array([[[10, 8, 1, 0]], [[9, 7, 5, 2]]], np.int64)
+    place, covered = NP.expert_assignment(f, np.array([[2], [2]]))
+    assert covered and place[:, 0].tolist() == [[1, 0, 1, 0], [0, 1, 0, 1]]
+
+
 def test_costs_and_migration_rule_match_oracle():
     rng = np.random.default_rng(3)
     N, L, E = 3, 4, 20

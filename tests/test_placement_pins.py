@@ -96,6 +96,40 @@ def test_count_allocation_infeasible_and_degenerate_inputs():
     assert cnt.tolist() == [[2, 2]]
 
 
+def test_count_allocation_donor_is_the_largest_over_provisioned_layer():
+    # two servers with room for 8 and shares 1/8, 3/8, 4/8 -> [1, 3, 4] each, totals [2, 6, 8]; E = 4:
+    # layer 0 is short by two and both other layers have spare experts.  Server 0: layer 2 (8 > 6)
+    # gives -> totals [3, 6, 7]; server 1: layer 2 again (7 > 6).
+    v = np.array([[1.0, 3.0, 4.0], [1.0, 3.0, 4.0]])
+    cnt, ok = PO.count_allocation(v, [8.0, 8.0], 1.0, E=4)
+    assert ok and cnt.tolist() == [[2, 3, 3], [2, 3, 3]]
+
+
+def test_count_allocation_donor_is_chosen_afresh_for_every_server():
+    # shares 2/16, 7/16, 7/16 of room for 8 -> [1, 3, 3] on both servers, totals [2, 6, 6], E = 4:
+    # layer 0 is short by two.  Server 0: equal totals, the lower layer index (1) gives -> totals
+    # [3, 5, 6]; server 1: now layer 2 is the largest.
+    v = np.array([[2.0, 7.0, 7.0], [2.0, 7.0, 7.0]])
+    cnt, ok = PO.count_allocation(v, [8.0, 8.0], 1.0, E=4)
+    assert ok and cnt.tolist() == [[2, 2, 3], [2, 3, 2]]
+
+
+def test_count_allocation_a_layer_with_exactly_E_does_not_give():
+    # [1, 2, 1] with E = 2: layers 0 and 2 are short, layer 1 has exactly E and nothing to spare
+    cnt, ok = PO.count_allocation(np.array([[1.0, 2.0, 1.0]]), [4.0], 1.0, E=2)
+    assert not ok and cnt.tolist() == [[1, 2, 1]]
+
+
+def test_count_allocation_a_server_without_the_donor_layer_is_passed_over():
+    # E = 3.  Step 1: server 0 (room 8) -> [0, 3, 0] (capped), server 1 (room 8, shares 1/8, 0, 7/8)
+    # -> [1, 0, 3] (capped), server 2 (room 4) -> [0, 0, 3] (capped).  Totals [1, 3, 6]: layer 0
+    # needs two, only layer 2 has spare ones.  Visiting order 0, 1, 2: server 0 holds nothing of
+    # layer 2 and is passed over, servers 1 and 2 move one each.
+    v = np.array([[0.0, 1.0, 0.0], [1.0, 0.0, 7.0], [0.0, 0.0, 1.0]])
+    cnt, ok = PO.count_allocation(v, [8.0, 8.0, 4.0], 1.0, E=3)
+    assert ok and cnt.tolist() == [[0, 3, 0], [2, 0, 2], [1, 0, 2]]
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_count_allocation_conservation_laws(seed):
     rng = np.random.default_rng(seed)
@@ -141,6 +175,19 @@ def test_assignment_fewest_duplicates_first_and_ties():
     f = np.zeros((2, 1, 4), np.int64)
     place, covered = PO.assignment(f, np.array([[2], [2]]))
     assert covered and place[:, 0].tolist() == [[1, 0, 1, 0], [0, 1, 0, 1]]
+
+
+def test_assignment_top_n_ties_go_to_the_lower_index():
+    place, _ = PO.assignment(np.array([[[5, 5, 1]]], np.int64), np.array([[1]]))
+    assert place[0, 0].tolist() == [1, 0, 0]
+
+
+def test_assignment_repair_starts_with_the_server_with_fewest_duplicates():
+    # holdings {0,1}, {0,1,2}, {2}; expert 3 is uncovered.  Duplicates: 2, 3 and 1 -> server 2 goes
+    # first and swaps its only expert, 2 (server 1 holds it too), for 3; nothing is left to repair.
+    f = np.array([[[9, 8, 1, 0]], [[9, 8, 7, 1]], [[1, 2, 9, 3]]], np.int64)
+    place, covered = PO.assignment(f, np.array([[2], [3], [1]]))
+    assert covered and place[:, 0].tolist() == [[1, 1, 0, 0], [1, 1, 1, 0], [0, 0, 0, 1]]
 
 
 def test_assignment_cannot_cover_without_room():
