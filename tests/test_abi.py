@@ -117,3 +117,19 @@ def test_null_pointers_and_negative_tokens_are_rejected_before_any_launch():
                                None, None, None, None, None, None, None, 0, None) == 1
     with pytest.raises(P.PrismError):
         P.workspace_bytes(P.make_desc(100, 128, 8, 2), 4)
+
+
+def test_a_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """Without the built library the binding raises: there is no other path that could answer."""
+    from paper_2508_12851_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libprism.so"))
+    with pytest.raises(P.PrismError, match="not built"):
+        binding.load_library(build_if_missing=False)
+    # nothing in the package imports the oracle
+    pkg = os.path.join(ROOT, "paper_2508_12851_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for name in files:
+            if name.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, name)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), name
