@@ -20,6 +20,7 @@
 #include "prism_internal.h"
 
 namespace prism {
+static bool stream_tiles_apply(const prism_layer_desc& d, int T);
 namespace {
 
 // ---------------------------------------------------------------------------
@@ -266,6 +267,17 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
     return run_bf16_ffn<TileCfg<64, 128, 32, 3>, TileCfg<64, 128, 32, 3>, true>(
         d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
   }
+  // Batches of a few hundred tokens of a wide layer are still bound by streaming the weights
+  // once, but an expert now has up to a few hundred rows.  Per k-tile a workgroup can pull
+  // about twice as many bytes from the L2 into LDS as its share of the HBM stream brings, so
+  // the tile is twice as wide in weight rows (256) as in activation rows (128): the weights,
+  // which come from HBM, are then two thirds of what a workgroup loads.  (256 x 128 tiles:
+  // 0.50 ms for 256 tokens of the 4096 x 14336 layer with 5 of 8 experts hosted; 128 x 256:
+  // 0.43 ms; the 256 x 256 prefill tiles: 0.62 ms, their down projection has too few items
+  // to fill the machine.)  The down projection splits its contraction as for decode batches.
+  if (stream_tiles_apply(d, T))
+    return run_bf16_ffn<TileCfg<128, 256, 32, 6>, TileCfg<128, 256, 32, 6>, true>(
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
   // Prefill batch: 256 x 256 tiles (GEMM1: 128 gate + 128 up weight rows).  Very short
   // contractions (H or F of 64) get the shallowest ring.
   if (d.hidden >= 128 && d.ffn >= 128)
@@ -275,12 +287,19 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
       d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
 }
 
+// Batches between the decode and the prefill sizes of layers wide enough for the 6-stage ring.
+static bool stream_tiles_apply(const prism_layer_desc& d, int T) {
+  return T > kDecodeMaxTokens && T <= kStreamMaxTokens && d.hidden >= 256 && d.ffn >= 1024;
+}
+
 bool ffn_schedule_shapes(const prism_layer_desc& d, int T, int* bm1, int* nt1, int* bm2, int* nt2) {
+  const bool stream = stream_tiles_apply(d, T);
   const bool decode = T <= kDecodeMaxTokens;
-  const int bm = decode ? 64 : 256, bn = decode ? 128 : 256;   // both ring depths share the tile
+  // (row tile, weight rows per tile); all ring depths of a path share the tile
+  const int bm = stream ? 128 : decode ? 64 : 256, bn = stream ? 256 : decode ? 128 : 256;
   *bm1 = bm; *nt1 = ceil_div(d.ffn, bn / 2);
   *bm2 = bm; *nt2 = ceil_div(d.hidden, bn);
-  return decode;
+  return decode || stream;
 }
 
 }  // namespace prism

@@ -376,6 +376,17 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, kMfma - 1 - kReads - kPart, 0);
+      } else if constexpr (kMfma >= (kReads > kPart ? kReads : kPart) + 1) {
+        // fewer MFMAs per step: an operand read and a refill load share the gap after an MFMA
+        constexpr int kGaps = kReads > kPart ? kReads : kPart;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+#pragma unroll
+        for (int r = 0; r < kGaps; ++r) {
+          if (r < kReads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          if (r < kPart) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kMfma - 1 - kGaps, 0);
       }
     }
     stage = next_stage;

@@ -30,6 +30,7 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 constexpr int kDispatchChunk = 2048;   // assignments per dispatch block
 constexpr int kDecodeMaxTokens = 64;    // batches up to this size take the weight-streaming path
 constexpr int kDecodeSplits = 4;        // contraction slices of its down projection (4 beat 8 and 2 when timed)
+constexpr int kStreamMaxTokens = 512;   // wide bf16 layers: batches up to this size also split the down projection (expert_ffn.hip)
 constexpr int kMinTileM = 64;           // smallest row tile of the grouped GEMM (bounds table sizes)
 constexpr int kRouteTokTile = 16;       // tokens per router tile
 constexpr int kRouteMaxHSplit = 16;     // hidden-dimension slices of the decode router
@@ -42,7 +43,7 @@ struct Workspace {
   int32_t* tiles;          // 2 x [tile_table_ints]: schedules of the two grouped GEMMs
   void* h;                 // [(A + S*T) * F] layer dtype: silu(gate)*up
   void* y;                 // [(A + S*T) * H] layer dtype: expert outputs
-  float* part;             // decode batches: [kDecodeSplits][A + S*T][H] fp32 partial sums
+  float* part;             // batches up to kStreamMaxTokens: [kDecodeSplits][A + S*T][H] fp32 partial sums
   double* route_part;      // decode batches: [token tiles][kRouteMaxHSplit][route_col_tiles][64][4] fp64
   size_t total;
 };
@@ -83,13 +84,14 @@ static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
   w.tiles = (int32_t*)take(2 * tile_table_ints(d, T) * 4);
   w.h = take(rows * d.ffn * es);
   w.y = take(rows * d.hidden * es);
-  // The decode-only regions are reserved for every T (sized for min(T, kDecodeMaxTokens)
-  // tokens), so that the total never shrinks as T grows: a workspace sized for max_tokens
-  // serves every smaller batch.
+  // The regions of the small-batch paths are reserved for every T (sized for min(T, limit of
+  // the path) tokens), so that the total never shrinks as T grows: a workspace sized for
+  // max_tokens serves every smaller batch.
   const size_t t_dec = (size_t)(T < kDecodeMaxTokens ? T : kDecodeMaxTokens);
-  const size_t rows_dec = t_dec * (size_t)(d.top_k + d.n_shared);
+  const size_t t_str = (size_t)(T < kStreamMaxTokens ? T : kStreamMaxTokens);
+  const size_t rows_str = t_str * (size_t)(d.top_k + d.n_shared);
   const bool bf16 = d.dtype == PRISM_BF16;
-  w.part = (float*)take(bf16 ? (size_t)kDecodeSplits * rows_dec * d.hidden * 4 : 0);
+  w.part = (float*)take(bf16 ? (size_t)kDecodeSplits * rows_str * d.hidden * 4 : 0);
   w.route_part = (double*)take(bf16 ? (size_t)ceil_div((int)t_dec, kRouteTokTile) * kRouteMaxHSplit *
                                           route_col_tiles(d.n_experts) * 64 * 4 * 8 : 0);
   w.total = off;

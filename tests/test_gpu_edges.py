@@ -24,8 +24,18 @@ def test_batch_sizes_around_tile_and_path_boundaries(T):
     print(f"T={T}: out err {err:.3g}")
 
 
+@pytest.mark.parametrize("T", [64, 65, 127, 128, 129, 257, 512, 513])
+def test_batch_sizes_of_a_wide_layer_around_the_tile_and_path_boundaries(T):
+    """H >= 256 and F >= 1024: batches of 65..512 tokens take 128 x 256 tiles and a split down
+    projection; 64 and 513 are the neighbouring paths."""
+    cfg = make_config("cfg2_mixtral_prefill", T=T, H=256, F=1024)
+    inp = make_inputs(cfg)
+    err = check_layer(cfg, run_layer(cfg, inp), oracle_layer(inp))
+    print(f"T={T}: out err {err:.3g}")
+
+
 @pytest.mark.parametrize("T", [24, 300])
-@pytest.mark.parametrize("H,F", [(64, 64), (128, 64), (64, 192), (192, 128), (128, 1024)])
+@pytest.mark.parametrize("H,F", [(64, 64), (128, 64), (64, 192), (192, 128), (128, 1024), (256, 1024)])
 def test_shortest_contractions(T, H, F):
     """H or F of 64..192: the k-tile ring is as long as the whole contraction."""
     cfg = make_config("cfg4_finegrained", T=T, H=H, F=F, E=12, k=3, S=1, n_local=7,
@@ -35,11 +45,11 @@ def test_shortest_contractions(T, H, F):
     print(f"T={T} H={H} F={F}: out err {err:.3g}")
 
 
-@pytest.mark.parametrize("T", [40, 700])
-def test_one_expert_takes_every_token(T):
+@pytest.mark.parametrize("T,F", [(40, 448), (700, 448), (400, 1024)])
+def test_one_expert_takes_every_token(T, F):
     """A +1000 bias sends slot 0 of every token to expert 3: one group with T rows (several
     row tiles), the other hosted experts nearly empty."""
-    cfg = make_config("cfg2_mixtral_prefill", T=T, H=256, F=448)
+    cfg = make_config("cfg2_mixtral_prefill", T=T, H=256, F=F)
     inp = make_inputs(cfg)
     inp.bias[:, 3] += 1000.0
     inp.mask[3] = 1
@@ -79,9 +89,9 @@ def test_other_stream_accumulated_counts_and_stage_events():
             assert events[2 * s - 1].elapsed_time(events[2 * s]) >= 0.0
 
 
-@pytest.mark.parametrize("T", [20, 300])
-def test_workspace_sized_for_a_larger_batch(T):
-    cfg = make_config("cfg4_finegrained", T=T, H=128, F=192, bias_group_tokens=64)
+@pytest.mark.parametrize("T,H,F", [(20, 128, 192), (300, 128, 192), (300, 256, 1088)])
+def test_workspace_sized_for_a_larger_batch(T, H, F):
+    cfg = make_config("cfg4_finegrained", T=T, H=H, F=F, bias_group_tokens=64)
     inp = make_inputs(cfg)
     ws = P.alloc_workspace(desc_of(cfg), 2048)
     ws.fill_(0xA5)

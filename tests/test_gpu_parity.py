@@ -35,6 +35,10 @@ CASES = {
     # few big experts: the 256-row tile configuration (several row tiles and a ragged last one)
     "two_big_experts": dict(name="cfg2_mixtral_prefill", T=1100, H=256, F=448, E=2, k=2, n_local=1),
     "three_big_experts": dict(name="cfg2_mixtral_prefill", T=1500, H=192, F=320, E=3, k=2, n_local=2),
+    # batches between the decode and the prefill sizes (256 x 128 tiles, split down projection)
+    "mixtral_mid": dict(name="cfg2_mixtral_prefill", T=200, H=256, F=1024),
+    "finegrained_mid": dict(name="cfg4_finegrained", T=300, H=256, F=1088, bias_group_tokens=128),
+    "one_big_expert_mid": dict(name="cfg2_mixtral_prefill", T=500, H=256, F=1024, E=2, k=2, n_local=1),
 }
 
 

@@ -35,6 +35,7 @@ CASES = {
     "short_contraction": dict(name="cfg4_finegrained", T=300, H=64, F=192, E=12, k=3, S=1, n_local=7,
                               bias_group_tokens=0),
     "two_big_experts": dict(name="cfg2_mixtral_prefill", T=1100, H=256, F=448, E=2, k=2, n_local=1),
+    "mixtral_mid": dict(name="cfg2_mixtral_prefill", T=200, H=256, F=1024),
     # decode batches whose shapes take the 32-wide k-tiles of the tiled layout (8-stage ring)
     "mixtral_decode_wide": dict(name="cfg3_mixtral_decode", T=32, H=512, F=1536),
     "finegrained_decode_wide": dict(name="cfg4_finegrained", T=50, H=256, F=1088, bias_group_tokens=16),
