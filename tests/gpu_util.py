@@ -48,14 +48,20 @@ def oracle_layer(inp, mask=None, x=None, token_pos=None, renormalize=True):
                        token_pos, renormalize)
 
 
-def rel_err(a, ref):
-    """max |a - ref| / (|ref| + rms(ref)): the layer-output error measure."""
+def rel_err(a, ref, per_row=False):
+    """max |a - ref| / (|ref| + rms(ref)): the layer-output error measure.  per_row: the rms of
+    the element's own row (token) instead of the whole array -- for batches whose tokens differ
+    widely in magnitude (a zero row of ref then demands an exactly zero row of a)."""
     a = np.asarray(a, np.float64)
     ref = np.asarray(ref, np.float64)
-    rms = np.sqrt(np.mean(ref ** 2)) if ref.size else 0.0
     if ref.size == 0:
         return 0.0
-    return float(np.max(np.abs(a - ref) / (np.abs(ref) + rms + 1e-300)))
+    if per_row:
+        rms = np.sqrt(np.mean(ref ** 2, axis=-1, keepdims=True))
+    else:
+        rms = np.sqrt(np.mean(ref ** 2))
+    diff = np.abs(a - ref)
+    return float(np.max(np.where(diff == 0, 0.0, diff / (np.abs(ref) + rms + 1e-300))))
 
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
@@ -73,7 +79,7 @@ def run_layer(cfg, inp, mask=None, wt=None, ws=None, gate_mode="renormalized",
     return o
 
 
-def check_layer(cfg, o, ref):
+def check_layer(cfg, o, ref, per_row=False):
     """Integer outputs bit-exact, gates to 1e-6, layer output within the dtype's tolerance."""
     nl, nr = o.n_local_remote.cpu().tolist()
     assert np.array_equal(o.topk_idx.cpu().numpy(), ref.route.topk_idx)
@@ -83,6 +89,6 @@ def check_layer(cfg, o, ref):
     assert np.array_equal(o.remote_src.cpu().numpy()[:nr], ref.dispatch.remote_src)
     assert np.array_equal(o.remote_offsets.cpu().numpy(), ref.dispatch.remote_offsets)
     assert np.array_equal(o.remote_bytes.cpu().numpy(), ref.dispatch.remote_bytes)
-    err = rel_err(to_f32(o.out), ref.out)
+    err = rel_err(to_f32(o.out), ref.out, per_row)
     assert err <= TOL[cfg.dtype], err
     return err
