@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--mask", choices=("top", "random"), default="top",
                     help="hosted experts: the most popular ones (what the first loop of Alg. 2 hosts) or a "
                          "seeded uniformly random subset of the same size (the uniform baseline of Sec. IV)")
+    ap.add_argument("--tokens", type=int, default=None,
+                    help="another batch size for the chosen workload's layer (not the benchmark line: "
+                         "config.workload then says so)")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the measured MFMA / HBM ceilings of this GPU")
     args = ap.parse_args()
@@ -127,9 +130,19 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(1)
     cfg = CONFIGS[args.config]
+    overrides = {}
     if args.mask == "random":
-        cfg = make_config(args.config, mask_kind="random")
-    decode = cfg.T <= 64
+        overrides["mask_kind"] = "random"
+    if args.tokens is not None:
+        if args.tokens < 1:
+            log("bench.py: --tokens must be at least 1")
+            sys.exit(2)
+        overrides["T"] = args.tokens
+    if overrides:
+        cfg = make_config(args.config, **overrides)
+    workload = cfg.name if args.tokens is None else f"{cfg.name} layer with {cfg.T} tokens"
+    # up to 512 tokens the dominant kernel streams the hosted weights once: HBM roofline
+    decode = cfg.T <= (64 if args.tokens is None else 512)
     steps = args.steps if args.steps is not None else (200 if decode else 30)
     warmup = args.warmup if args.warmup is not None else (20 if decode else 5)
 
@@ -220,7 +233,7 @@ def main():
         alg_bytes = touched * 2 * cfg.H * cfg.F * es + cfg.T * cfg.H * es + rows * cfg.F * es
         achieved = alg_bytes / (dom_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": achieved / PEAK_HBM_GBS, "traffic": read_traffic(cfg.name),
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": read_traffic(cfg.name) if args.tokens is None else None,
                     "kernel": "grouped_gemm_kernel<gated> (gate/up projection + silu*up)",
                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": dom_ms}
     else:
@@ -228,7 +241,7 @@ def main():
         achieved = alg_flop / (dom_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_BF16_TFLOPS,
-                    "traffic": read_traffic(cfg.name),
+                    "traffic": read_traffic(cfg.name) if args.tokens is None else None,
                     "kernel": "grouped_gemm_kernel<gated> (gate/up projection + silu*up)",
                     "algorithmic_flop_per_launch": alg_flop, "kernel_ms": dom_ms}
     layer_flop = 2.0 * cfg.T * cfg.H * cfg.E + 6.0 * cfg.H * cfg.F * rows
@@ -242,7 +255,7 @@ def main():
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": cfg.name, "tokens": cfg.T, "hidden": cfg.H, "ffn": cfg.F,
+        "config": {"workload": workload, "tokens": cfg.T, "hidden": cfg.H, "ffn": cfg.F,
                    "experts": cfg.E, "top_k": cfg.k, "shared_experts": cfg.S,
                    "local_experts": int(inp.mask.sum()), "n_local": n_local, "n_remote": n_remote,
                    "remote_bytes_each_way": int(out.remote_bytes[0]),

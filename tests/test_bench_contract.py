@@ -62,3 +62,15 @@ def test_bench_options_show_up_in_the_config_it_reports():
     assert 0 <= c["tokens_with_a_remote_slot"] <= c["tokens"]
     assert c["n_local"] + c["n_remote"] == c["tokens"] * c["top_k"]
     assert "cpu_baseline" not in d and "measured_ceilings" not in d
+
+
+@pytest.mark.gpu
+def test_bench_with_another_batch_size_says_so():
+    r = subprocess.run([sys.executable, BENCH, "--config", "cfg3_mixtral_decode", "--tokens", "100", "--steps", "3",
+                        "--warmup", "1", "--no-cpu-baseline", "--no-ceilings"],
+                       capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads(r.stdout.strip())
+    assert d["config"]["tokens"] == 100 and "100 tokens" in d["config"]["workload"]
+    assert d["roofline"]["bound"] == "hbm" and d["roofline"]["traffic"] is None
+    assert d["value"] == pytest.approx(100 / (d["ms_per_step"] * 1e-3), rel=1e-6)
