@@ -125,11 +125,14 @@ def test_debug_check_finds_a_hosted_expert_without_weights():
     P.prism_debug_check_weights(desc, weight_table(inp, holes), to_dev(holes))
 
 
-def test_prefill_layer_graph_replay_equals_eager():
+@pytest.mark.parametrize("T,H,F", [(2500, 128, 192), (300, 256, 1088)])
+def test_prefill_layer_graph_replay_equals_eager(T, H, F):
     """A prefill layer (staged router, two-launch dispatch with the schedule workgroups, both GEMMs,
-    combine) captured in a graph and replayed with the workspace and outputs poisoned in between
-    gives the eager result every time: the library allocates nothing and needs no memset node."""
-    cfg = make_config("cfg4_finegrained", T=2500, H=128, F=192, bias_group_tokens=512)
+    combine) and one of a few hundred tokens (single dispatch workgroup, schedule launch, split down
+    projection, slice-summing combine) captured in a graph and replayed with the workspace and
+    outputs poisoned in between give the eager result every time: the library allocates nothing
+    and needs no memset node."""
+    cfg = make_config("cfg4_finegrained", T=T, H=H, F=F, bias_group_tokens=512)
     inp = make_inputs(cfg)
     desc = desc_of(cfg)
     ws = P.alloc_workspace(desc, cfg.T)
