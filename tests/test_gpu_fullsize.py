@@ -81,6 +81,22 @@ def test_cfg3_mixtral_decode_full_size():
     print(f"cfg3 full size: out err {err:.3g}")
 
 
+@pytest.mark.parametrize("T", [200, 512])
+def test_mixtral_shape_between_decode_and_prefill_full_size(T):
+    """The full Mixtral layer shape at a few hundred tokens (128 x 256 tiles, split down
+    projection with 112 k-tiles per slice), tiled weights as bench.py uses them."""
+    from prism_inputs import make_config
+    cfg = make_config("cfg2_mixtral_prefill", T=T)
+    inp = make_inputs(cfg, weights="local", threads=16)
+    desc = desc_of(cfg, weight_layout="tiled")
+    o = P.prism_moe_layer(desc, to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias),
+                          weight_table(inp, tiled=True), to_dev(inp.mask), P.alloc_workspace(desc, cfg.T))
+    torch.cuda.synchronize()
+    _check_integers(cfg, inp, o)
+    err = _check_sampled_output(cfg, inp, o, 32, seed=20 + T)
+    print(f"Mixtral shape, {T} tokens: sampled out err {err:.3g}")
+
+
 def test_cfg4_finegrained_full_size():
     cfg = CONFIGS["cfg4_finegrained"]
     inp = make_inputs(cfg, weights="local", threads=16)
