@@ -268,13 +268,13 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
         d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
   }
   // Batches of a few hundred tokens of a wide layer are still bound by streaming the weights
-  // once, but an expert now has up to a few hundred rows.  Per k-tile a workgroup can pull
-  // about twice as many bytes from the L2 into LDS as its share of the HBM stream brings, so
-  // the tile is twice as wide in weight rows (256) as in activation rows (128): the weights,
-  // which come from HBM, are then two thirds of what a workgroup loads.  (256 x 128 tiles:
-  // 0.50 ms for 256 tokens of the 4096 x 14336 layer with 5 of 8 experts hosted; 128 x 256:
-  // 0.43 ms; the 256 x 256 prefill tiles: 0.62 ms, their down projection has too few items
-  // to fill the machine.)  The down projection splits its contraction as for decode batches.
+  // once, but an expert now has up to a few hundred rows.  Tiles twice as wide in weight rows
+  // (256) as in activation rows (128) bring twice the HBM bytes per k-tile for the same waits
+  // and barriers, and the padding rows of a half-empty 256-row tile would cost their loads and
+  // MFMAs like real ones.  (256 x 128 tiles: 0.50 ms for 256 tokens of the 4096 x 14336 layer
+  // with 5 of 8 experts hosted; 128 x 256: 0.43 ms; the 256 x 256 prefill tiles: 0.62 ms,
+  // their down projection has too few items to fill the machine.)  The down projection splits
+  // its contraction as for decode batches.
   if (stream_tiles_apply(d, T))
     return run_bf16_ffn<TileCfg<128, 256, 32, 6>, TileCfg<128, 256, 32, 6>, true>(
         d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
