@@ -2,11 +2,11 @@
  * prism.h -- C ABI of libprism: one edge server's placement-aware MoE layer
  * forward on one AMD MI355X (gfx950), as hand-written HIP kernels.
  *
- * Paper: "Prism" (arXiv 2508.12851), Sec. III-A (system architecture: each
- * server's gating network picks experts "whether local or remote", local
- * experts run, results are aggregated, gating decisions are logged for the
- * global scheduler) and Sec. III-B (activation frequency f_n^l(e), placement
- * z_{n,g}^e, indicator 1_remote(n,e), proxy objective Eq. 2).
+ * Paper: Prism (arXiv 2508.12851), Sec. III-A (system architecture: a server's
+ * gating network picks a token's experts wherever they are hosted, the hosted
+ * ones run on that server, the outputs are summed, and the picks are reported
+ * to the global scheduler) and Sec. III-B (activation frequency f_n^l(e),
+ * placement z_{n,g}^e, indicator 1_remote(n,e), proxy objective Eq. 2).
  *
  * The paper fixes the roles of the steps, not their formulas; this library
  * uses the standard top-k softmax gating and bias-free SwiGLU experts of the
@@ -165,8 +165,8 @@ prism_status prism_route(const prism_layer_desc* desc, const void* x, const void
  *   n_local_remote [2] int32 out: {n_local, n_remote}
  *   remote_bytes   [2] int64 out: {bytes to send, bytes to receive} =
  *                  n_remote * H * sizeof(element) each (one activation row per
- *                  remote assignment each way, Sec. III-B "transmitting
- *                  activations ... sending results back")
+ *                  remote assignment each way: the traffic of a remote call,
+ *                  Sec. III-B)
  */
 prism_status prism_dispatch(const prism_layer_desc* desc, const int32_t* topk_idx,
                             const uint8_t* local_mask, int32_t T, int32_t* local_src,
@@ -190,8 +190,8 @@ prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
                               size_t workspace_bytes, void* stream);
 
 /*
- * Gate-weighted aggregation of the local expert outputs (Sec. III-A
- * "aggregated"): out[t] = sum over local slots j (ascending) of
+ * Gate-weighted aggregation of the local expert outputs (the last step of
+ * the layer in Sec. III-A): out[t] = sum over local slots j (ascending) of
  * topk_gate[t,j] * y[row of (t,j)], then + shared rows s = 0..S-1, in fp32,
  * rounded once to the layer dtype.  A token with no local slot and S == 0
  * gets zeros.
@@ -202,9 +202,9 @@ prism_status prism_combine(const prism_layer_desc* desc, const void* y, const in
                            void* out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The two ends of the remote call on the requesting server (Sec. III-A: "a
- * remote call is initiated ... the results of experts are transmitted back ...
- * where they are aggregated"; Sec. III-B: what travels is the activation).
+ * The two ends of the remote call on the requesting server (Sec. III-A: the
+ * request to the hosting server and the aggregation of what it returns;
+ * Sec. III-B: what travels is the activation).
  *
  * prism_pack_remote gathers the activation rows to ship, in remote-list order:
  *   packed[r] = x[remote_src[r] / k]  for r < remote_offsets[E]
@@ -241,6 +241,23 @@ prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const 
                              int32_t* remote_src, int32_t* remote_offsets,
                              int32_t* n_local_remote, int64_t* remote_bytes, void* workspace,
                              size_t workspace_bytes, void* stream);
+
+/*
+ * The permutation the placement split of Sec. III-B produced inside the last whole-layer
+ * call (prism_moe_layer, prism_moe_layer_traced) that used `workspace` with the same desc
+ * and T: that call keeps local_src / local_offsets in the workspace, this one copies them
+ * out (device-to-device copies enqueued on `stream`; enqueue it on the layer's stream, or
+ * after that call has finished, and before the workspace is used again).
+ *   local_src     [T*k] int32 out, as prism_dispatch defines it; entries past n_local
+ *                 hold whatever the workspace held
+ *   local_offsets [E+1] int32 out
+ *   inv           [T*k] int32 out or NULL: row of assignment a in the layer's y, -1 if remote
+ * Errors: as the layer call (INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL); PRISM_ERR_LAUNCH
+ * if a copy cannot be enqueued.
+ */
+prism_status prism_layer_permutation(const prism_layer_desc* desc, int32_t T, const void* workspace,
+                                     size_t workspace_bytes, int32_t* local_src,
+                                     int32_t* local_offsets, int32_t* inv, void* stream);
 
 /*
  * prism_moe_layer with stage timing for measurement harnesses.  stage_events

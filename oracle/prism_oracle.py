@@ -26,8 +26,8 @@ standard definitions of the two model families it evaluates, Sec. IV):
              no biases, for every local assignment, and for every
              (token, shared expert).
   combine    out[t] = sum_{local slots j} gate[t,j] * y[(t,j)] + sum_s y_sh[s,t]
-             ("results of experts are ... aggregated", Sec. III-A); remote
-             slots contribute nothing here (their rows arrive later).
+             (the aggregation step of Sec. III-A); remote slots contribute
+             nothing here (their rows arrive later).
   pack_remote / combine_remote
              the two ends of the remote call: the activation rows shipped for the
              remote list, and the returned expert outputs added, gate-weighted, to
@@ -114,7 +114,10 @@ def route(x: np.ndarray, w_router: np.ndarray, bias: Optional[np.ndarray], k: in
     E = w64.shape[0]
     if not (1 <= k <= E):
         raise ValueError("need 1 <= k <= E")
-    logits = (x64 @ w64.T).astype(np.float32)          # fp64 sum, one rounding
+    acc = np.zeros((T, E), dtype=np.float64)
+    for h in range(H):                                 # fp64 sum in index order h = 0, 1, ...
+        acc += x64[:, h:h + 1] * w64[:, h][None, :]
+    logits = acc.astype(np.float32)                    # one rounding
     if bias is not None:
         b = np.asarray(bias, dtype=np.float32).reshape(-1, E)
         pos = np.arange(T) if token_pos is None else np.asarray(token_pos)
@@ -242,9 +245,9 @@ def combine(y: np.ndarray, local_src: np.ndarray, topk_gate: np.ndarray, T: int,
 
 
 # ---------------------------------------------------------------------------
-# the remote call (Sec. III-A: a remote call is initiated, "the results of experts
-# are transmitted back ... where they are aggregated"; Sec. III-B: what is shipped
-# is the activation, the hosting server executes the expert, results come back)
+# the remote call (Sec. III-A: the requesting server asks the hosting server and
+# aggregates what comes back; Sec. III-B: what is shipped is the activation, the
+# hosting server executes the expert, results return)
 # ---------------------------------------------------------------------------
 
 def pack_remote(x: np.ndarray, remote_src: np.ndarray, k: int) -> np.ndarray:

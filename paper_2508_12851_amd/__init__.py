@@ -7,5 +7,5 @@ from .binding import (  # noqa: F401
     load_library, make_desc, prism_combine, prism_dispatch, prism_expert_ffn, prism_moe_layer,
     prism_route, torch_dtype, workspace_bytes, LIB_PATH, SYMBOLS, STAGES,
     prism_ceiling_mfma_bf16, prism_ceiling_hbm_read, prism_pack_remote, prism_combine_remote,
-    prism_debug_check_weights, prism_pack_weights,
+    prism_debug_check_weights, prism_pack_weights, prism_layer_permutation, LayerPermutation,
 )

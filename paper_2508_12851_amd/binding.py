@@ -20,7 +20,8 @@ PRISM_F32, PRISM_BF16 = 0, 1
 SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism_dispatch",
            "prism_expert_ffn", "prism_combine", "prism_moe_layer", "prism_moe_layer_traced",
            "prism_ceiling_mfma_bf16", "prism_ceiling_hbm_read", "prism_pack_remote",
-           "prism_combine_remote", "prism_debug_check_weights", "prism_pack_weights")
+           "prism_combine_remote", "prism_debug_check_weights", "prism_pack_weights",
+           "prism_layer_permutation")
 STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
 GATE_MODES = {"renormalized": 0, "softmax_all": 1}
 WEIGHT_LAYOUTS = {"row_major": 0, "tiled": 1}
@@ -73,6 +74,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.prism_pack_remote.argtypes = [dp, vp, vp, vp, i32, vp, vp]
     lib.prism_combine_remote.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.prism_pack_weights.argtypes = [vp, i32, i32, vp, vp]
+    lib.prism_layer_permutation.argtypes = [dp, i32, vp, sz, vp, vp, vp, vp]
     lib.prism_debug_check_weights.argtypes = [dp, wp, vp, ctypes.POINTER(i32)]
     lib.prism_ceiling_mfma_bf16.argtypes = [vp, vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.prism_ceiling_hbm_read.argtypes = [vp, sz, vp, i32, vp]
@@ -271,6 +273,26 @@ def prism_moe_layer(desc: LayerDesc, x, w_router, router_bias, weights: WeightTa
                                           _ptr(workspace), workspace.numel(), _stream(stream)),
            "prism_moe_layer")
     return o
+
+
+@dataclass
+class LayerPermutation:
+    local_src: torch.Tensor
+    local_offsets: torch.Tensor
+    inv: torch.Tensor
+
+
+def prism_layer_permutation(desc: LayerDesc, T: int, workspace, stream=None) -> LayerPermutation:
+    """Copies of the permutation the last whole-layer call left in `workspace` (see prism.h)."""
+    i32 = dict(dtype=torch.int32, device=workspace.device)
+    A = T * desc.top_k
+    p = LayerPermutation(torch.full((A,), -1, **i32), torch.empty((desc.n_experts + 1,), **i32),
+                         torch.empty((A,), **i32))
+    _check(load_library().prism_layer_permutation(ctypes.byref(desc), T, _ptr(workspace),
+                                                  workspace.numel(), _ptr(p.local_src),
+                                                  _ptr(p.local_offsets), _ptr(p.inv), _stream(stream)),
+           "prism_layer_permutation")
+    return p
 
 
 def prism_ceiling_mfma_bf16(operands, out, n_workgroups: int, iters: int, stream=None) -> float:

@@ -78,6 +78,7 @@ prism_status prism_workspace_bytes(const prism_layer_desc* desc, int32_t max_tok
 prism_status prism_route(const prism_layer_desc* desc, const void* x, const void* w_router,
                          const float* router_bias, int32_t T, float* logits, int32_t* topk_idx,
                          float* topk_gate, int32_t* counts, int64_t* counts_accum, void* stream) {
+  PRISM_ENTER();
   PRISM_TRY(validate_desc(desc, T, false));
   PRISM_RETURN_IF(counts == nullptr, PRISM_ERR_INVALID_ARG);
   if (T > 0)
@@ -92,6 +93,7 @@ prism_status prism_dispatch(const prism_layer_desc* desc, const int32_t* topk_id
                             int32_t* local_offsets, int32_t* remote_src, int32_t* remote_offsets,
                             int32_t* n_local_remote, int64_t* remote_bytes, void* workspace,
                             size_t workspace_bytes, void* stream) {
+  PRISM_ENTER();
   PRISM_TRY(validate_desc(desc, T, false));
   PRISM_RETURN_IF(local_mask == nullptr || local_offsets == nullptr || remote_offsets == nullptr ||
                       n_local_remote == nullptr || remote_bytes == nullptr,
@@ -110,6 +112,7 @@ prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
                               const prism_expert_weights* weights, const int32_t* local_src,
                               const int32_t* local_offsets, int32_t T, void* y, void* workspace,
                               size_t workspace_bytes, void* stream) {
+  PRISM_ENTER();
   PRISM_TRY(validate_desc(desc, T, true));
   PRISM_TRY(check_weights(*desc, weights));
   PRISM_RETURN_IF(local_offsets == nullptr, PRISM_ERR_INVALID_ARG);
@@ -123,6 +126,7 @@ prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
 prism_status prism_combine(const prism_layer_desc* desc, const void* y, const int32_t* local_src,
                            const int32_t* local_offsets, const float* topk_gate, int32_t T,
                            void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  PRISM_ENTER();
   PRISM_TRY(validate_desc(desc, T, true));
   PRISM_RETURN_IF(local_offsets == nullptr, PRISM_ERR_INVALID_ARG);
   if (T > 0)
@@ -137,6 +141,7 @@ prism_status prism_combine(const prism_layer_desc* desc, const void* y, const in
 
 prism_status prism_pack_remote(const prism_layer_desc* desc, const void* x, const int32_t* remote_src,
                                const int32_t* remote_offsets, int32_t T, void* packed, void* stream) {
+  PRISM_ENTER();
   PRISM_TRY(validate_desc(desc, T, false));
   PRISM_RETURN_IF(remote_offsets == nullptr, PRISM_ERR_INVALID_ARG);
   if (T > 0) PRISM_RETURN_IF(x == nullptr || remote_src == nullptr || packed == nullptr, PRISM_ERR_INVALID_ARG);
@@ -147,6 +152,7 @@ prism_status prism_combine_remote(const prism_layer_desc* desc, const void* y_re
                                   const int32_t* remote_src, const int32_t* remote_offsets,
                                   const float* topk_gate, int32_t T, void* out, void* workspace,
                                   size_t workspace_bytes, void* stream) {
+  PRISM_ENTER();
   PRISM_TRY(validate_desc(desc, T, false));
   PRISM_RETURN_IF(remote_offsets == nullptr, PRISM_ERR_INVALID_ARG);
   if (T > 0)
@@ -160,6 +166,7 @@ prism_status prism_combine_remote(const prism_layer_desc* desc, const void* y_re
 }
 
 prism_status prism_pack_weights(const void* src, int32_t rows, int32_t cols, void* dst, void* stream) {
+  PRISM_ENTER();
   PRISM_RETURN_IF(src == nullptr || dst == nullptr || rows < 1 || cols < 1, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF((((uintptr_t)src | (uintptr_t)dst) & 15u) != 0, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(rows % 16 != 0 || cols % 32 != 0, PRISM_ERR_UNSUPPORTED);
@@ -208,6 +215,7 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                                     int32_t* remote_offsets, int32_t* n_local_remote,
                                     int64_t* remote_bytes, void* workspace, size_t workspace_bytes,
                                     void* stream, void* const* stage_events) {
+  PRISM_ENTER();
   PRISM_TRY(validate_desc(desc, T, true));
   PRISM_TRY(check_weights(*desc, weights));
   PRISM_RETURN_IF(local_mask == nullptr || counts == nullptr || remote_offsets == nullptr ||
@@ -247,6 +255,26 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
   trace(ev, PRISM_STAGE_COMBINE, 0, st);
   PRISM_TRY(launch_combine(*desc, ws.y, ws.inv, topk_gate, T, out, st, ws.part, n_splits));
   trace(ev, PRISM_STAGE_COMBINE, 1, st);
+  return PRISM_OK;
+}
+
+prism_status prism_layer_permutation(const prism_layer_desc* desc, int32_t T, const void* workspace,
+                                     size_t workspace_bytes, int32_t* local_src,
+                                     int32_t* local_offsets, int32_t* inv, void* stream) {
+  PRISM_ENTER();
+  PRISM_TRY(validate_desc(desc, T, true));
+  PRISM_RETURN_IF(local_offsets == nullptr, PRISM_ERR_INVALID_ARG);
+  if (T > 0) PRISM_RETURN_IF(local_src == nullptr, PRISM_ERR_INVALID_ARG);
+  Workspace ws;
+  PRISM_TRY(check_workspace(*desc, T, const_cast<void*>(workspace), workspace_bytes, &ws));
+  const hipStream_t st = (hipStream_t)stream;
+  const size_t A = (size_t)T * desc->top_k;
+  auto copy = [&](void* dst, const void* src, size_t bytes) {
+    return bytes == 0 || hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st) == hipSuccess;
+  };
+  if (!copy(local_offsets, ws.local_offsets, (size_t)(desc->n_experts + 1) * 4) ||
+      !copy(local_src, ws.local_src, A * 4) || (inv != nullptr && !copy(inv, ws.inv, A * 4)))
+    return PRISM_ERR_LAUNCH;
   return PRISM_OK;
 }
 

@@ -61,6 +61,7 @@ extern "C" {
 
 prism_status prism_ceiling_mfma_bf16(const void* operands, float* out, int32_t n_workgroups,
                                      int32_t iters, double* flop, void* stream) {
+  PRISM_ENTER();
   PRISM_RETURN_IF(operands == nullptr || out == nullptr || flop == nullptr, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(n_workgroups < 1 || iters < 1, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(((uintptr_t)operands & 15u) != 0, PRISM_ERR_INVALID_ARG);
@@ -74,6 +75,7 @@ prism_status prism_ceiling_mfma_bf16(const void* operands, float* out, int32_t n
 
 prism_status prism_ceiling_hbm_read(const void* src, size_t bytes, void* out, int32_t n_workgroups,
                                     void* stream) {
+  PRISM_ENTER();
   PRISM_RETURN_IF(src == nullptr || out == nullptr, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(n_workgroups < 1 || bytes < 16, PRISM_ERR_INVALID_ARG);
   PRISM_RETURN_IF(((uintptr_t)src & 15u) != 0 || ((uintptr_t)out & 15u) != 0, PRISM_ERR_INVALID_ARG);

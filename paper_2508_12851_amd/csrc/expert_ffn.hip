@@ -1,5 +1,5 @@
 // Grouped SwiGLU expert FFN over the locally hosted and the shared experts
-// (paper Sec. III-A: "experts resident on the server compute on routed tokens").
+// (paper Sec. III-A: the local expert execution of a server).
 //
 //   GEMM1  h[r, f] = silu( x[tok(r)] . W_gate^e[f] ) * ( x[tok(r)] . W_up^e[f] )
 //   GEMM2  y[r, n] = h[r] . W_down^e[n]

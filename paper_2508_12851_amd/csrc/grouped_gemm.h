@@ -220,9 +220,15 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     const int gi = it.g < p.E ? it.g : it.g - p.E;
     r.b0 = t0[gi];
     r.b1 = t1[gi];
-    if (GATED)   // entry j of the LDS slot = local_src[row_start + j]; past the end reads 0
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(src_rsrc, (lds_ptr_t)src_lds, 16, lane * 16,
-                                               it.row_start * 4, 0, 0);
+    // Entry j of the LDS slot = local_src[row_start + j].  The whole byte offset sits in the
+    // per-lane operand, which the hardware checks against the buffer size (a scalar offset
+    // would escape that check), so entries past the end of local_src arrive as zeros instead
+    // of being read.  Shared-expert tiles take their tokens from tok_base: their load is
+    // issued out of range on purpose, which keeps the count of loads in flight uniform.
+    if (GATED)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          src_rsrc, (lds_ptr_t)src_lds, 16,
+          it.tok_base >= 0 ? kOutOfRange : (uint32_t)it.row_start * 4u + (uint32_t)lane * 16u, 0, 0, 0);
     return r;
   };
   // Byte offset of this lane's 16-byte chunk c of weight row n in k-tile 0 (the k-tile offset
@@ -597,10 +603,8 @@ prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int
   constexpr int kCusPerXcd = 32;
   constexpr int kResident = (160 * 1024) / smem;     // workgroups per CU that fit in LDS
   auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK, ROTATE>;
-  // once per instantiation (thread-safe initialisation of a local static)
-  static const bool attr_ok =
-      hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem) == hipSuccess;
-  if (!attr_ok) return PRISM_ERR_LAUNCH;
+  static LdsLimitOnce lds_limit;   // one per instantiation
+  if (!raise_lds_limit(lds_limit, (const void*)kernel, smem)) return PRISM_ERR_LAUNCH;
   if (capacity <= 0) return PRISM_OK;
   const int splits = SPLITK ? n_splits : 1;
   int slots = kCusPerXcd * kResident / splits;       // persistent workgroups per XCD

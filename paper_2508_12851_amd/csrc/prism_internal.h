@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "prism.h"
 
 namespace prism {
@@ -104,7 +106,30 @@ static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
 prism_status validate_desc(const prism_layer_desc* d, int32_t T, bool need_ffn_shapes);
 
 #define PRISM_RETURN_IF(cond, code) do { if (cond) return (code); } while (0)
+// A launch reports its failure through the thread's last-error slot only, and that slot also
+// keeps whatever an earlier, unrelated HIP call of this thread left there.  Every entry point
+// of the ABI therefore empties the slot first (PRISM_ENTER), so that PRISM_CHECK_LAUNCH sees
+// the errors of this call's launches alone.
+#define PRISM_ENTER() do { (void)hipGetLastError(); } while (0)
 #define PRISM_CHECK_LAUNCH() do { if (hipGetLastError() != hipSuccess) return PRISM_ERR_LAUNCH; } while (0)
+
+// Raises a kernel's dynamic-LDS limit once per device (bit d of `done`: raised on device d);
+// an attempt that fails is repeated by the next call instead of being remembered.
+struct LdsLimitOnce {
+  std::atomic<uint32_t> done{0};
+};
+static inline bool raise_lds_limit(LdsLimitOnce& once, const void* kernel, int bytes) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  const uint32_t bit = 1u << (dev & 31);
+  if (once.done.load(std::memory_order_acquire) & bit) return true;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  once.done.fetch_or(bit, std::memory_order_release);
+  return true;
+}
 #define PRISM_TRY(expr) do { prism_status s__ = (expr); if (s__ != PRISM_OK) return s__; } while (0)
 
 // ---------------------------------------------------------------------------

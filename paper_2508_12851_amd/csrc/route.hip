@@ -566,11 +566,9 @@ prism_status launch_staged_one(const prism_layer_desc& d, const void* x, const v
                                const float* bias, int T, float* logits, int32_t* idx, float* gate,
                                int32_t* counts, int64_t* accum, hipStream_t st) {
   using C = StagedCfg<NT, TMB>;
-  // more than 64 KiB of dynamic LDS: raised once per instantiation (thread-safe local static)
-  static const bool attr_ok =
-      hipFuncSetAttribute((const void*)route_staged_kernel<NT, TMB>,
-                          hipFuncAttributeMaxDynamicSharedMemorySize, C::kLdsBytes) == hipSuccess;
-  if (!attr_ok) return PRISM_ERR_LAUNCH;
+  static LdsLimitOnce lds_limit;   // more than 64 KiB of dynamic LDS; one per instantiation
+  if (!raise_lds_limit(lds_limit, (const void*)route_staged_kernel<NT, TMB>, C::kLdsBytes))
+    return PRISM_ERR_LAUNCH;
   hipLaunchKernelGGL((route_staged_kernel<NT, TMB>), dim3(ceil_div(T, kTokPerBlock * TMB)),
                      dim3(kWavesPerBlock * kWave), (size_t)C::kLdsBytes, st, (const uint16_t*)x,
                      (const uint16_t*)w, bias, T, d.hidden, d.n_experts, d.top_k,
@@ -603,16 +601,14 @@ prism_status launch_typed(const prism_layer_desc& d, const void* x, const void* 
   const int h_span = route_h_span(d.hidden);
   const dim3 grid(ceil_div(T, kTokPerBlock), partial != nullptr ? ceil_div(d.hidden, h_span) : 1);
   const dim3 block(kWavesPerBlock * kWave);
-  // the 256-expert tile needs 128 KiB of LDS for the partial sums; raised once (thread-safe
-  // initialisation of a local static)
-  static const bool attr_ok = [] {
+  // the 256-expert tile needs 128 KiB of LDS for the partial sums
+  if (nt > 8) {
+    static LdsLimitOnce lds_full, lds_partial;
     const int bytes = (kWavesPerBlock / 2) * 16 * 4 * 64 * 8;
-    return hipFuncSetAttribute((const void*)route_kernel<TIn, 16, false>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess &&
-           hipFuncSetAttribute((const void*)route_kernel<TIn, 16, true>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
-  }();
-  if (!attr_ok) return PRISM_ERR_LAUNCH;
+    if (!raise_lds_limit(lds_full, (const void*)route_kernel<TIn, 16, false>, bytes) ||
+        !raise_lds_limit(lds_partial, (const void*)route_kernel<TIn, 16, true>, bytes))
+      return PRISM_ERR_LAUNCH;
+  }
 #define PRISM_ROUTE_LAUNCH(NT, PARTIAL)                                                          \
   hipLaunchKernelGGL((route_kernel<TIn, NT, PARTIAL>), grid, block,                              \
                      (size_t)(kWavesPerBlock / 2) * NT * 4 * 64 * 8, st, (const TIn*)x, (const TIn*)w,  \

@@ -75,8 +75,20 @@ def run_layer(cfg, inp, mask=None, wt=None, ws=None, gate_mode="renormalized",
     wt = weight_table(inp, mask) if wt is None else wt
     o = P.prism_moe_layer(desc, to_dev(inp.x), to_dev(inp.w_router), to_dev(inp.bias), wt,
                           to_dev(mask), ws, **kw)
+    # the permutation the layer call itself built (it lives in the workspace)
+    o.perm = P.prism_layer_permutation(desc, cfg.T, ws, stream=kw.get("stream"))
     torch.cuda.synchronize()
     return o
+
+
+def check_permutation(perm, dispatch_ref, A):
+    """local_src / local_offsets / inverse of a layer call, bit for bit against oracle.dispatch."""
+    nl = dispatch_ref.n_local
+    assert np.array_equal(perm.local_offsets.cpu().numpy(), dispatch_ref.local_offsets)
+    assert np.array_equal(perm.local_src.cpu().numpy()[:nl], dispatch_ref.local_src)
+    inv = np.full(A, -1, dtype=np.int32)
+    inv[dispatch_ref.local_src] = np.arange(nl, dtype=np.int32)
+    assert np.array_equal(perm.inv.cpu().numpy(), inv)
 
 
 def check_layer(cfg, o, ref, per_row=False):
@@ -89,6 +101,8 @@ def check_layer(cfg, o, ref, per_row=False):
     assert np.array_equal(o.remote_src.cpu().numpy()[:nr], ref.dispatch.remote_src)
     assert np.array_equal(o.remote_offsets.cpu().numpy(), ref.dispatch.remote_offsets)
     assert np.array_equal(o.remote_bytes.cpu().numpy(), ref.dispatch.remote_bytes)
+    if getattr(o, "perm", None) is not None:
+        check_permutation(o.perm, ref.dispatch, cfg.A)
     err = rel_err(to_f32(o.out), ref.out, per_row)
     assert err <= TOL[cfg.dtype], err
     return err

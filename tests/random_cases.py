@@ -1,0 +1,42 @@
+"""Seeded random layer shapes, batch sizes, masks, gate conventions and weight layouts (all
+within the library's documented limits), shared by the GPU parity test that runs them and
+the CPU test that settles which error measure each of them is held to.  No arithmetic of the
+method lives here."""
+import os
+
+import numpy as np
+
+N_CASES = int(os.environ.get("PRISM_RANDOM_CASES", "32"))   # more for a longer hunt
+
+# Cases whose layer output is held to the per-row form of the error measure, max |a - ref| /
+# (|ref| + rms of the token's own row), instead of the whole-batch rms: their tokens differ by
+# orders of magnitude in size (256 experts, a random mask, gates that are not renormalised),
+# and the bf16 roundings the layer is defined with, carried out in otherwise exact arithmetic,
+# already exceed the 2e-2 bar against the whole-batch rms.  tests/test_error_measure.py proves
+# this membership on the CPU, case by case, and that no other case needs it.
+PER_ROW_CASES = frozenset({12})
+
+
+def draw_case(i):
+    """-> (make_config overrides, gate mode, tiled weights?) of random case i."""
+    rng = np.random.default_rng(7000 + i)
+    pick = lambda seq: seq[int(rng.integers(0, len(seq)))]
+    f32 = i % 8 == 7
+    E = pick([2, 3, 5, 8, 12, 16, 40, 60, 64, 100, 256])
+    k = int(rng.integers(1, min(8, E) + 1))
+    S = pick([0, 0, 0, 1, 2, 4])
+    if f32:
+        H, F = pick([8, 72, 136]), pick([24, 200])
+    else:
+        H, F = pick([64, 128, 192, 256, 320, 512, 1024]), pick([64, 128, 192, 448, 1024, 1088, 1536])
+    T = int(pick([rng.integers(1, 65), rng.integers(65, 513), rng.integers(513, 1500)]))
+    if f32:
+        T = min(T, 200)
+    # keep the fp64 oracle to a few seconds
+    while T * (k + S) * H * F > 3e9 and T > 1:
+        T = max(1, T // 2)
+    n_local = int(pick([0, E, rng.integers(0, E + 1), rng.integers(0, E + 1)]))
+    return dict(dtype="f32" if f32 else "bf16", T=T, H=H, F=F, E=E, k=k, S=S, n_local=n_local,
+                n_swapped=0, bias_group_tokens=pick([0, 0, 16, 64, 128]), mask_kind=pick(["top", "random"]),
+                zipf_s=pick([0.0, 1.0, 1.2]), seed=100 + i), \
+        pick(["renormalized", "softmax_all"]), (not f32) and H % 32 == 0 and F % 32 == 0 and bool(rng.integers(0, 2))

@@ -43,6 +43,10 @@ def test_bench_prints_one_json_line_with_the_contract_keys(config, bound, unit):
     assert rf["bound"] == bound and rf["unit"] == unit
     assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"], rel=1e-9)
     assert 0 < rf["frac"] < 1 and rf["kernel_ms"] > 0
+    lr = d["layer_roofline"]                       # the same bound over the whole step
+    assert lr["bound"] == bound and lr["unit"] == unit and 0 < lr["frac"] < 1
+    assert lr["frac"] == pytest.approx(lr["achieved"] / lr["peak"], rel=1e-9)
+    assert rf["traffic"] is None or rf["traffic"] > 0
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["unit"] == "tokens/s" and cb["value"] > 0 and cb["cores"] >= 1
     assert "sample" in cb and "8" in cb["sample"]
@@ -74,3 +78,52 @@ def test_bench_with_another_batch_size_says_so():
     assert d["config"]["tokens"] == 100 and "100 tokens" in d["config"]["workload"]
     assert d["roofline"]["bound"] == "hbm" and d["roofline"]["traffic"] is None
     assert d["value"] == pytest.approx(100 / (d["ms_per_step"] * 1e-3), rel=1e-6)
+
+
+@pytest.mark.gpu
+def test_default_run_carries_both_halves_of_the_metric():
+    """No --config: the prefill batch is the line's value, the decode batch of the same layer sits
+    under `decode`, each with the dominant kernel's and the whole layer's roofline fraction."""
+    r = subprocess.run([sys.executable, BENCH, "--steps", "3", "--warmup", "1", "--cpu-sample-tokens", "8",
+                        "--no-ceilings"], capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    assert d["config"]["workload"] == "cfg2_mixtral_prefill" and d["steps"] == 3
+    assert d["roofline"]["bound"] == "mfma" and d["layer_roofline"]["bound"] == "mfma"
+    assert d["value"] == pytest.approx(4096 / (d["ms_per_step"] * 1e-3), rel=1e-6)
+    dec = d["decode"]
+    assert dec["workload"] == "cfg3_mixtral_decode" and dec["config"]["tokens"] == 32
+    assert dec["config"]["weight_copies_rotated"] == 4
+    for key in ("roofline", "layer_roofline"):
+        assert dec[key]["bound"] == "hbm" and dec[key]["unit"] == "GB/s" and 0 < dec[key]["frac"] < 1
+    assert dec["layer_roofline"]["achieved"] == pytest.approx(
+        dec["layer_roofline"]["algorithmic_bytes_per_step"] / (dec["ms_per_step"] * 1e-3) / 1e9, rel=1e-6)
+    assert dec["tokens_per_s"] == pytest.approx(32 / (dec["ms_per_step"] * 1e-3), rel=1e-6)
+
+
+@pytest.mark.gpu
+def test_migration_workload_reports_every_phase():
+    base = [sys.executable, BENCH, "--config", "cfg5_dsv2lite_migration", "--steps", "3", "--warmup", "1",
+            "--no-cpu-baseline", "--no-ceilings"]
+    r = subprocess.run(base, capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads(r.stdout.strip())
+    ph = d["phases"]
+    assert [p["workload"] for p in ph] == ["cfg5_dsv2lite_migration phase 0", "cfg5_dsv2lite_migration phase 1"]
+    for p in ph:
+        c = p["config"]
+        assert sum(p["counts"]) == 8192 * 6 and c["n_local"] + c["n_remote"] == 8192 * 6
+        assert c["remote_bytes_each_way"] == c["n_remote"] * 2048 * 2
+        assert p["tokens_per_s"] == pytest.approx(8192 / (p["ms_per_step"] * 1e-3), rel=1e-6)
+    assert ph[0]["counts"] != ph[1]["counts"]                     # the popularity ranking was reshuffled
+    total_ms = sum(p["ms_per_step"] for p in ph) * 3
+    assert d["value"] == pytest.approx(2 * 8192 * 3 / (total_ms * 1e-3), rel=1e-6)
+    assert d["migration"] == {"experts_admitted": 16, "experts_evicted": 16,
+                              "bytes_loaded": 16 * 3 * 2048 * 1408 * 2, "changed_entries_eq3": 32}
+    r = subprocess.run(base + ["--phase", "1"], capture_output=True, text=True, timeout=900)
+    assert r.returncode == 0, r.stderr[-2000:]
+    one = json.loads(r.stdout.strip())
+    assert "phases" not in one and one["config"]["workload"] == "cfg5_dsv2lite_migration"
+    assert one["config"]["n_remote"] == ph[1]["config"]["n_remote"]

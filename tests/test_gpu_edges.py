@@ -160,3 +160,43 @@ def test_prefill_layer_graph_replay_equals_eager(T, H, F):
         assert torch.equal(out.out, eager["out"]) and torch.equal(out.topk_idx, eager["topk_idx"]), i
         assert torch.equal(out.counts, eager["counts"]) and torch.equal(out.remote_bytes, eager["remote_bytes"])
         assert torch.equal(out.remote_src[:nr], eager["remote_src"][:nr])
+
+
+@pytest.mark.parametrize("T,S", [(37, 0), (333, 2), (901, 1)])
+def test_expert_ffn_with_local_src_at_the_very_end_of_its_allocation(T, S):
+    """prism_expert_ffn is handed a local_src of exactly T*k ints (T*k odd, so its last 16-byte
+    piece is cut short) that ends where its allocation ends: the kernel's prefetch of a row
+    tile's source rows must neither depend on anything past that end nor change a result.
+    Shared-expert tiles (S > 0) take no source rows at all."""
+    from oracle import prism_oracle as O
+
+    from gpu_util import TOL, rel_err, to_f32
+
+    cfg = make_config("cfg4_finegrained", T=T, H=256, F=448, E=6, k=3, S=S, n_local=4,
+                      bias_group_tokens=0)
+    inp = make_inputs(cfg)
+    f = inp.f32
+    desc = desc_of(cfg)
+    ws = P.alloc_workspace(desc, cfg.T)
+    r = O.route(f(inp.x), f(inp.w_router), inp.bias, cfg.k, cfg.bias_group_tokens)
+    d = O.dispatch(r.topk_idx, inp.mask, cfg.H, cfg.es)
+    A = cfg.A
+    assert A % 4 != 0
+    src = np.full(A, -1, np.int32)
+    src[:d.n_local] = d.local_src
+    # the list occupies the last A ints of a larger buffer whose front is poisoned
+    buf = torch.full((4096 + A,), 0x7FFFFFF0, dtype=torch.int32, device="cuda")
+    tail = buf[4096:]
+    tail.copy_(torch.from_numpy(src))
+    offsets = to_dev(d.local_offsets)
+    wt = weight_table(inp)
+    x = to_dev(inp.x)
+    y_tail = P.prism_expert_ffn(desc, x, wt, tail, offsets, ws)
+    y_plain = P.prism_expert_ffn(desc, x, wt, to_dev(src), offsets, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y_tail, y_plain)
+    y_ref = O.expert_ffn(f(inp.x), lambda e: tuple(f(w) for w in inp.expert(e)),
+                         [tuple(f(w) for w in inp.shared(s)) for s in range(S)], d.local_src,
+                         d.local_offsets, cfg.k)
+    got = to_f32(y_tail)
+    assert rel_err(np.concatenate([got[:d.n_local], got[A:]]), y_ref) <= TOL[cfg.dtype]

@@ -2,47 +2,20 @@
 conventions and weight layouts (all within the documented limits): what the hand-picked cases
 of the other files might miss.  Every case prints its parameters before it runs.
 
-The output error is taken relative to |ref| + rms of the token's own row: with random masks, up to
-256 experts and gates that are not renormalised, tokens differ by orders of magnitude in size, and
-the bf16 rounding of a large token's expert rows, measured against the rms of the whole batch,
-exceeds the 2e-2 bar in exact arithmetic too (case 12: 0.0235 for a CPU emulation that rounds only
-where the layer stores bf16)."""
-import os
-
+The output error is max |a - ref| / (|ref| + rms(ref)) with the rms of the whole batch, for every
+stage of every case but one: the layer output of the cases in random_cases.PER_ROW_CASES is
+measured against the rms of the token's own row, because the bf16 roundings the layer is defined
+with exceed the bar against the batch rms there in exact arithmetic (shown on the CPU by
+tests/test_error_measure.py, which also shows that no other case needs it)."""
 import numpy as np
 import pytest
 
 from prism_inputs import make_config, make_inputs
+from random_cases import N_CASES, PER_ROW_CASES, draw_case
 
 from gpu_util import check_layer, oracle_layer, run_layer, weight_table
 
 pytestmark = pytest.mark.gpu
-
-N_CASES = int(os.environ.get("PRISM_RANDOM_CASES", "32"))   # more for a longer hunt
-
-
-def draw_case(i):
-    rng = np.random.default_rng(7000 + i)
-    pick = lambda seq: seq[int(rng.integers(0, len(seq)))]
-    f32 = i % 8 == 7
-    E = pick([2, 3, 5, 8, 12, 16, 40, 60, 64, 100, 256])
-    k = int(rng.integers(1, min(8, E) + 1))
-    S = pick([0, 0, 0, 1, 2, 4])
-    if f32:
-        H, F = pick([8, 72, 136]), pick([24, 200])
-    else:
-        H, F = pick([64, 128, 192, 256, 320, 512, 1024]), pick([64, 128, 192, 448, 1024, 1088, 1536])
-    T = int(pick([rng.integers(1, 65), rng.integers(65, 513), rng.integers(513, 1500)]))
-    if f32:
-        T = min(T, 200)
-    # keep the fp64 oracle to a few seconds
-    while T * (k + S) * H * F > 3e9 and T > 1:
-        T = max(1, T // 2)
-    n_local = int(pick([0, E, rng.integers(0, E + 1), rng.integers(0, E + 1)]))
-    return dict(dtype="f32" if f32 else "bf16", T=T, H=H, F=F, E=E, k=k, S=S, n_local=n_local,
-                n_swapped=0, bias_group_tokens=pick([0, 0, 16, 64, 128]), mask_kind=pick(["top", "random"]),
-                zipf_s=pick([0.0, 1.0, 1.2]), seed=100 + i), \
-        pick(["renormalized", "softmax_all"]), (not f32) and H % 32 == 0 and F % 32 == 0 and bool(rng.integers(0, 2))
 
 
 @pytest.mark.parametrize("i", range(N_CASES))
@@ -54,7 +27,7 @@ def test_layer_parity_on_a_random_shape(i):
     ref = oracle_layer(inp, renormalize=gate_mode == "renormalized")
     o = run_layer(cfg, inp, wt=weight_table(inp, tiled=tiled), gate_mode=gate_mode,
                   weight_layout="tiled" if tiled else "row_major")
-    err = check_layer(cfg, o, ref, per_row=True)
+    err = check_layer(cfg, o, ref, per_row=i in PER_ROW_CASES)
     print(f"case {i}: out err {err:.3g}, n_local {ref.dispatch.n_local}, n_remote {ref.dispatch.n_remote}")
 
 
@@ -103,12 +76,12 @@ def test_separate_calls_parity_on_a_random_shape(i):
     torch.cuda.synchronize()
     yg = to_f32(y)
     y_got = np.concatenate([yg[:nl], yg[cfg.A:]])                 # shared rows start at T*k
-    assert rel_err(y_got, y_ref, per_row=True) <= TOL[cfg.dtype]
+    assert rel_err(y_got, y_ref) <= TOL[cfg.dtype]
 
     out_ref = O.combine(y_ref, d_ref.local_src, r_ref.topk_gate, cfg.T, cfg.S, cfg.dtype)
     out = P.prism_combine(desc, y, d.local_src, d.local_offsets, r.topk_gate, ws)
     torch.cuda.synchronize()
-    assert rel_err(to_f32(out), out_ref, per_row=True) <= TOL[cfg.dtype]
+    assert rel_err(to_f32(out), out_ref, per_row=i in PER_ROW_CASES) <= TOL[cfg.dtype]
 
     # the remote call: ship, execute on a peer that hosts everything, add the returned rows
     packed = P.prism_pack_remote(desc, x, d.remote_src, d.remote_offsets)
@@ -123,10 +96,10 @@ def test_separate_calls_parity_on_a_random_shape(i):
         y_rem = P.prism_expert_ffn(peer, packed[:nr].contiguous(), wt, rows, d.remote_offsets,
                                    P.alloc_workspace(peer, nr))
         y_rem_ref = O.expert_ffn(f(inp.x), experts, [], d_ref.remote_src, d_ref.remote_offsets, cfg.k)
-        assert rel_err(to_f32(y_rem), y_rem_ref, per_row=True) <= TOL[cfg.dtype]
+        assert rel_err(to_f32(y_rem), y_rem_ref) <= TOL[cfg.dtype]
         P.prism_combine_remote(desc, y_rem, d.remote_src, d.remote_offsets, r.topk_gate, out, ws)
         torch.cuda.synchronize()
         done_ref = O.combine_remote(out_ref, y_rem_ref, d_ref.remote_src, r_ref.topk_gate, cfg.dtype)
-        err = rel_err(to_f32(out), done_ref, per_row=True)
+        err = rel_err(to_f32(out), done_ref)
         assert err <= 1.5 * TOL[cfg.dtype], err                   # one more bf16 rounding on the way
     print(f"case {i}: n_local {nl}, n_remote {nr}: all stages agree")

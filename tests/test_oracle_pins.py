@@ -48,6 +48,7 @@ def _brute_route(x, w, bias_rows, k):
     E = w.shape[0]
     idx = np.zeros((T, k), dtype=np.int32)
     gate = np.zeros((T, k), dtype=np.float64)
+    logits = np.zeros((T, E), dtype=np.float32)
     for t in range(T):
         lg = []
         for e in range(E):
@@ -58,13 +59,14 @@ def _brute_route(x, w, bias_rows, k):
             if bias_rows is not None:
                 v = np.float32(v + np.float32(bias_rows[t][e]))
             lg.append(v)
+        logits[t] = lg
         order = sorted(range(E), key=lambda e: (-float(lg[e]), e))[:k]
         full = np.exp(np.array([float(v) for v in lg]) - max(float(v) for v in lg))
         full = full / full.sum()           # full softmax over all E experts ...
         sel = full[order]
         gate[t] = sel / sel.sum()          # ... renormalised over the k picked
         idx[t] = order
-    return idx, gate
+    return idx, gate, logits
 
 
 def test_route_matches_brute_force_full_sort():
@@ -75,7 +77,8 @@ def test_route_matches_brute_force_full_sort():
     bias = rng.standard_normal((3, E)).astype(np.float32)
     r = O.route(x, w, bias, k, bias_group_tokens=8)
     rows = [bias[t // 8] for t in range(T)]
-    bidx, bgate = _brute_route(x, w, rows, k)
+    bidx, bgate, blogits = _brute_route(x, w, rows, k)
+    assert np.array_equal(r.logits, blogits)           # same sum order: the same fp32 bits
     assert np.array_equal(r.topk_idx, bidx)
     assert np.max(np.abs(r.topk_gate - bgate)) < 1e-6
 
