@@ -243,6 +243,33 @@ prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const 
                              size_t workspace_bytes, void* stream);
 
 /*
+ * prism_moe_layer for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * same layer, the same kernels, the same results bit for bit; the scratch memory is a fixed
+ * array of PRISM_STATIC_SCRATCH_BYTES that lives in the library's device image (every GPU
+ * the process uses holds its own copy until the process ends).  The call allocates and frees
+ * nothing, and neither does anything it calls.
+ *   - Accepted while prism_workspace_bytes(desc, T) <= PRISM_STATIC_SCRATCH_BYTES (32 MiB:
+ *     e.g. decode batches of up to 64 tokens of a 4096 x 14336 layer with 8 experts, 2048
+ *     tokens of a 256 x 448 layer); beyond that PRISM_ERR_WORKSPACE_TOO_SMALL, nothing launched.
+ *   - The first call on a device looks up that device's address of the array (one
+ *     hipGetSymbolAddress; PRISM_ERR_LAUNCH if it fails); make that call outside any capture.
+ *   - All calls on one GPU share the one array, which keeps the previous call's contents
+ *     (no step of the layer reads scratch it has not written in the same call, so nothing
+ *     needs clearing): calls that overlap in time on one GPU -- two streams, two threads --
+ *     race on it.  Run them on one stream, or give the others prism_moe_layer and a workspace.
+ *   - prism_layer_permutation does not apply (there is no workspace to name).
+ * Other arguments, outputs and errors as prism_moe_layer.
+ */
+#define PRISM_STATIC_SCRATCH_BYTES (32u << 20)
+prism_status prism_moe_layer_static(const prism_layer_desc* desc, const void* x, const void* w_router,
+                                    const float* router_bias, const prism_expert_weights* weights,
+                                    const uint8_t* local_mask, int32_t T, void* out, int32_t* topk_idx,
+                                    float* topk_gate, int32_t* counts, int64_t* counts_accum,
+                                    int32_t* remote_src, int32_t* remote_offsets,
+                                    int32_t* n_local_remote, int64_t* remote_bytes, void* stream);
+
+/*
  * The permutation the placement split of Sec. III-B produced inside the last whole-layer
  * call (prism_moe_layer, prism_moe_layer_traced) that used `workspace` with the same desc
  * and T: that call keeps local_src / local_offsets in the workspace, this one copies them

@@ -21,7 +21,7 @@ SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism
            "prism_expert_ffn", "prism_combine", "prism_moe_layer", "prism_moe_layer_traced",
            "prism_ceiling_mfma_bf16", "prism_ceiling_hbm_read", "prism_pack_remote",
            "prism_combine_remote", "prism_debug_check_weights", "prism_pack_weights",
-           "prism_layer_permutation")
+           "prism_layer_permutation", "prism_moe_layer_static")
 STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
 GATE_MODES = {"renormalized": 0, "softmax_all": 1}
 WEIGHT_LAYOUTS = {"row_major": 0, "tiled": 1}
@@ -71,6 +71,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.prism_moe_layer.argtypes = [dp, vp, vp, vp, wp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                     vp, sz, vp]
     lib.prism_moe_layer_traced.argtypes = lib.prism_moe_layer.argtypes + [vp]
+    lib.prism_moe_layer_static.argtypes = lib.prism_moe_layer.argtypes[:16] + [vp]
     lib.prism_pack_remote.argtypes = [dp, vp, vp, vp, i32, vp, vp]
     lib.prism_combine_remote.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.prism_pack_weights.argtypes = [vp, i32, i32, vp, vp]
@@ -272,6 +273,25 @@ def prism_moe_layer(desc: LayerDesc, x, w_router, router_bias, weights: WeightTa
                                           _ptr(o.n_local_remote), _ptr(o.remote_bytes),
                                           _ptr(workspace), workspace.numel(), _stream(stream)),
            "prism_moe_layer")
+    return o
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def prism_moe_layer_static(desc: LayerDesc, x, w_router, router_bias, weights: WeightTable, local_mask,
+                           outputs: LayerOut, counts_accum=None, stream=None) -> LayerOut:
+    """The layer on the library's fixed scratch array: no workspace, nothing allocated (the caller
+    supplies every output buffer)."""
+    o = outputs
+    _check(load_library().prism_moe_layer_static(ctypes.byref(desc), _ptr(x), _ptr(w_router),
+                                                 _ptr(router_bias), ctypes.byref(weights.struct),
+                                                 _ptr(local_mask), x.shape[0], _ptr(o.out),
+                                                 _ptr(o.topk_idx), _ptr(o.topk_gate), _ptr(o.counts),
+                                                 _ptr(counts_accum), _ptr(o.remote_src),
+                                                 _ptr(o.remote_offsets), _ptr(o.n_local_remote),
+                                                 _ptr(o.remote_bytes), _stream(stream)),
+           "prism_moe_layer_static")
     return o
 
 

@@ -50,6 +50,33 @@ static prism_status check_weights(const prism_layer_desc& d, const prism_expert_
   return PRISM_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Scratch memory of prism_moe_layer_static: a fixed device array instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy at its own address; `scratch`
+// itself is only a host-side handle of the symbol, the device address comes from
+// hipGetSymbolAddress (once per device, with that device current) and is what the kernels get.
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = PRISM_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static prism_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PRISM_ERR_LAUNCH;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    // two threads racing here ask for the same address; either store is fine
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return PRISM_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return PRISM_OK;
+}
+
 }  // namespace prism
 
 using namespace prism;
@@ -289,6 +316,23 @@ prism_status prism_moe_layer(const prism_layer_desc* desc, const void* x, const 
                                 topk_idx, topk_gate, counts, counts_accum, remote_src,
                                 remote_offsets, n_local_remote, remote_bytes, workspace,
                                 workspace_bytes, stream, nullptr);
+}
+
+prism_status prism_moe_layer_static(const prism_layer_desc* desc, const void* x, const void* w_router,
+                                    const float* router_bias, const prism_expert_weights* weights,
+                                    const uint8_t* local_mask, int32_t T, void* out, int32_t* topk_idx,
+                                    float* topk_gate, int32_t* counts, int64_t* counts_accum,
+                                    int32_t* remote_src, int32_t* remote_offsets,
+                                    int32_t* n_local_remote, int64_t* remote_bytes, void* stream) {
+  PRISM_ENTER();
+  PRISM_TRY(validate_desc(desc, T, true));
+  // the same layout the caller's workspace would have; it has to fit the fixed array
+  PRISM_RETURN_IF(carve(*desc, T, nullptr).total > kStaticScratchBytes, PRISM_ERR_WORKSPACE_TOO_SMALL);
+  void* ws = nullptr;
+  PRISM_TRY(static_scratch(&ws));
+  return prism_moe_layer_traced(desc, x, w_router, router_bias, weights, local_mask, T, out, topk_idx,
+                                topk_gate, counts, counts_accum, remote_src, remote_offsets,
+                                n_local_remote, remote_bytes, ws, kStaticScratchBytes, stream, nullptr);
 }
 
 #pragma GCC visibility pop
