@@ -358,6 +358,21 @@ prism_status prism_debug_check_weights(const prism_layer_desc* desc,
  *   src  device, 16-byte aligned;  out  device, n_workgroups * 256 * 16 bytes
  * Errors: PRISM_ERR_INVALID_ARG for NULL or misaligned pointers, counts < 1.
  */
+/*
+ * prism_ceiling_hbm_read_pattern: the streaming read with its access pattern as arguments,
+ * for finding the pattern this machine's memory system serves fastest.  The first
+ * floor(bytes / span_bytes) spans of src are read; workgroup b (256 threads) takes spans
+ * b, b + n_workgroups, ... and walks each with loads_in_flight (2, 4, 8 or 16) loads of 16
+ * bytes per thread in flight.  mode 0: loads into registers; 1: direct-to-LDS loads, 1 KiB per
+ * wavefront and instruction (what the grouped GEMM's operand rings issue); 2: loads marked
+ * non-temporal; 3: direct-to-LDS loads marked non-temporal.  span_bytes must be a multiple of 4096 * loads_in_flight, at most 2 GiB.
+ *   bytes_read  host, receives the bytes the launch reads;  out  device, n_workgroups * 4096 bytes
+ * Errors: INVALID_ARG (NULL, misaligned, counts < 1, unknown mode, fewer bytes than one
+ * span), UNSUPPORTED (loads_in_flight or span_bytes outside the above).
+ */
+prism_status prism_ceiling_hbm_read_pattern(const void* src, size_t bytes, void* out, int32_t n_workgroups,
+                                            int32_t loads_in_flight, size_t span_bytes, int32_t mode,
+                                            size_t* bytes_read, void* stream);
 prism_status prism_ceiling_mfma_bf16(const void* operands, float* out, int32_t n_workgroups,
                                      int32_t iters, double* flop, void* stream);
 prism_status prism_ceiling_hbm_read(const void* src, size_t bytes, void* out, int32_t n_workgroups,

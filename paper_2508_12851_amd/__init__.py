@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     prism_route, torch_dtype, workspace_bytes, LIB_PATH, SYMBOLS, STAGES,
     prism_ceiling_mfma_bf16, prism_ceiling_hbm_read, prism_pack_remote, prism_combine_remote,
     prism_debug_check_weights, prism_pack_weights, prism_layer_permutation, LayerPermutation,
-    prism_moe_layer_static, STATIC_SCRATCH_BYTES,
+    prism_moe_layer_static, STATIC_SCRATCH_BYTES, prism_ceiling_hbm_read_pattern,
 )

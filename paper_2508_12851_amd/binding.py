@@ -21,7 +21,7 @@ SYMBOLS = ("prism_status_string", "prism_workspace_bytes", "prism_route", "prism
            "prism_expert_ffn", "prism_combine", "prism_moe_layer", "prism_moe_layer_traced",
            "prism_ceiling_mfma_bf16", "prism_ceiling_hbm_read", "prism_pack_remote",
            "prism_combine_remote", "prism_debug_check_weights", "prism_pack_weights",
-           "prism_layer_permutation", "prism_moe_layer_static")
+           "prism_layer_permutation", "prism_moe_layer_static", "prism_ceiling_hbm_read_pattern")
 STAGES = ("route", "dispatch", "ffn_up", "ffn_down", "combine")
 GATE_MODES = {"renormalized": 0, "softmax_all": 1}
 WEIGHT_LAYOUTS = {"row_major": 0, "tiled": 1}
@@ -79,6 +79,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.prism_debug_check_weights.argtypes = [dp, wp, vp, ctypes.POINTER(i32)]
     lib.prism_ceiling_mfma_bf16.argtypes = [vp, vp, i32, i32, ctypes.POINTER(ctypes.c_double), vp]
     lib.prism_ceiling_hbm_read.argtypes = [vp, sz, vp, i32, vp]
+    lib.prism_ceiling_hbm_read_pattern.argtypes = [vp, sz, vp, i32, i32, sz, i32, ctypes.POINTER(sz), vp]
     for name in SYMBOLS:
         # without argtypes ctypes would pass a device address as a 32-bit int
         if getattr(lib, name).argtypes is None:
@@ -331,6 +332,18 @@ def prism_ceiling_hbm_read(src, out, n_workgroups: int, stream=None) -> int:
                                                  n_workgroups, _stream(stream)),
            "prism_ceiling_hbm_read")
     return nbytes // 16 * 16
+
+
+def prism_ceiling_hbm_read_pattern(src, out, n_workgroups: int, loads_in_flight: int, span_bytes: int,
+                                   mode: int, stream=None) -> int:
+    """Enqueues the streaming read with the given access pattern (see prism.h); returns the bytes read."""
+    n = ctypes.c_size_t(0)
+    _check(load_library().prism_ceiling_hbm_read_pattern(_ptr(src), ctypes.c_size_t(src.numel() * src.element_size()),
+                                                         _ptr(out), n_workgroups, loads_in_flight,
+                                                         ctypes.c_size_t(span_bytes), mode, ctypes.byref(n),
+                                                         _stream(stream)),
+           "prism_ceiling_hbm_read_pattern")
+    return n.value
 
 
 def prism_pack_remote(desc: LayerDesc, x, remote_src, remote_offsets, stream=None) -> torch.Tensor:

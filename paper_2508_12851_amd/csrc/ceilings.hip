@@ -51,6 +51,73 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restric
   if ((acc.x | acc.y | acc.z | acc.w) != 0) out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
 }
 
+// Streaming reads with the access pattern as parameters, to find what the memory system of the
+// machine at hand serves fastest.  The source is cut into spans of span16 16-byte units; workgroup
+// b takes spans b, b + gridDim.x, ... and walks each with its 256 threads, U loads of 16 bytes per
+// thread in flight.  MODE 0: plain loads into registers; 1: direct-to-LDS loads (no register
+// ever holds the data, as in the GEMM rings); 2: loads marked non-temporal; 3: direct-to-LDS
+// loads marked non-temporal (kNonTemporal in the instruction's cache-policy operand).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <int U, int MODE>
+__global__ __launch_bounds__(256) void stream_pattern_kernel(const u32x4* __restrict__ p, size_t n_spans,
+                                                             uint32_t span16, u32x4* __restrict__ out) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  constexpr bool kLds = MODE == 1 || MODE == 3;
+  __shared__ __align__(16) uint8_t s_sink[kLds ? 4 * U * 1024 : 16];
+  u32x4 acc = {0, 0, 0, 0};
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  for (size_t sp = blockIdx.x; sp < n_spans; sp += gridDim.x) {
+    const u32x4* q = p + sp * span16;
+    if (kLds) {
+      // a wavefront walks its quarter of the span, 1 KiB per load instruction, U in flight
+      const uint32_t per_wave = span16 / 4;                 // 16-byte units, a multiple of 64 U
+      const __amdgpu_buffer_rsrc_t r =
+          __builtin_amdgcn_make_buffer_rsrc((void*)(q + (size_t)wave * per_wave), 0, (int)(per_wave * 16), kBufferFlags);
+      uint8_t* base = s_sink + wave * (U * 1024);
+      for (uint32_t i = 0; i < per_wave; i += 64 * U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)(base + u * 1024), 16, lane * 16,
+                                                   (int)((i + u * 64) * 16), 0, MODE == 3 ? kNonTemporal : 0);
+        wait_vmcnt<U / 2>();                                // the older half has landed: keep the rest in flight
+      }
+    } else {
+      for (uint32_t i = threadIdx.x; i < span16; i += 256 * U) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          v[u] = MODE == 2 ? __builtin_nontemporal_load(q + i + u * 256) : q[i + u * 256];
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u];
+      }
+    }
+  }
+  if (kLds) {
+    wait_vmcnt<0>();
+    __syncthreads();
+    // what the wavefront's last trip left in its U slots (keeps the loads observable)
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      acc ^= *reinterpret_cast<const u32x4*>(s_sink + wave * (U * 1024) + u * 1024 + lane * 16);
+  }
+  // data-dependent store: an all-zero source is read without any write traffic
+  if ((acc.x | acc.y | acc.z | acc.w) != 0) out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
+#endif
+}
+
+template <int U>
+static bool launch_pattern(int mode, const u32x4* p, size_t n_spans, uint32_t span16, u32x4* out,
+                           int n_workgroups, hipStream_t st) {
+  const dim3 grid(n_workgroups), block(256);
+  if (mode == 0) hipLaunchKernelGGL((stream_pattern_kernel<U, 0>), grid, block, 0, st, p, n_spans, span16, out);
+  else if (mode == 1) hipLaunchKernelGGL((stream_pattern_kernel<U, 1>), grid, block, 0, st, p, n_spans, span16, out);
+  else if (mode == 2) hipLaunchKernelGGL((stream_pattern_kernel<U, 2>), grid, block, 0, st, p, n_spans, span16, out);
+  else if (mode == 3) hipLaunchKernelGGL((stream_pattern_kernel<U, 3>), grid, block, 0, st, p, n_spans, span16, out);
+  else return false;
+  return true;
+}
+
 }  // namespace
 }  // namespace prism
 
@@ -81,6 +148,34 @@ prism_status prism_ceiling_hbm_read(const void* src, size_t bytes, void* out, in
   PRISM_RETURN_IF(((uintptr_t)src & 15u) != 0 || ((uintptr_t)out & 15u) != 0, PRISM_ERR_INVALID_ARG);
   hipLaunchKernelGGL(stream_read_kernel, dim3(n_workgroups), dim3(256), 0, (hipStream_t)stream,
                      (const uint4*)src, bytes / 16, (uint4*)out);
+  PRISM_CHECK_LAUNCH();
+  return PRISM_OK;
+}
+
+prism_status prism_ceiling_hbm_read_pattern(const void* src, size_t bytes, void* out, int32_t n_workgroups,
+                                            int32_t loads_in_flight, size_t span_bytes, int32_t mode,
+                                            size_t* bytes_read, void* stream) {
+  PRISM_ENTER();
+  PRISM_RETURN_IF(src == nullptr || out == nullptr || bytes_read == nullptr, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(((uintptr_t)src & 15u) != 0 || ((uintptr_t)out & 15u) != 0, PRISM_ERR_INVALID_ARG);
+  PRISM_RETURN_IF(n_workgroups < 1 || mode < 0 || mode > 3, PRISM_ERR_INVALID_ARG);
+  const int U = loads_in_flight;
+  PRISM_RETURN_IF(U != 2 && U != 4 && U != 8 && U != 16, PRISM_ERR_UNSUPPORTED);
+  // a span is walked in trips of 256 threads x U loads x 16 bytes; it must hold whole trips
+  const size_t trip = (size_t)4096 * U;
+  PRISM_RETURN_IF(span_bytes < trip || span_bytes % trip != 0 || span_bytes > ((size_t)1 << 31), PRISM_ERR_UNSUPPORTED);
+  const size_t n_spans = bytes / span_bytes;
+  PRISM_RETURN_IF(n_spans < 1, PRISM_ERR_INVALID_ARG);
+  *bytes_read = n_spans * span_bytes;
+  const u32x4* p = (const u32x4*)src;
+  const uint32_t span16 = (uint32_t)(span_bytes / 16);
+  const hipStream_t st = (hipStream_t)stream;
+  bool ok = false;
+  if (U == 2) ok = launch_pattern<2>(mode, p, n_spans, span16, (u32x4*)out, n_workgroups, st);
+  else if (U == 4) ok = launch_pattern<4>(mode, p, n_spans, span16, (u32x4*)out, n_workgroups, st);
+  else if (U == 8) ok = launch_pattern<8>(mode, p, n_spans, span16, (u32x4*)out, n_workgroups, st);
+  else ok = launch_pattern<16>(mode, p, n_spans, span16, (u32x4*)out, n_workgroups, st);
+  PRISM_RETURN_IF(!ok, PRISM_ERR_INVALID_ARG);
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;
 }

@@ -112,8 +112,12 @@ template <int BK> __device__ __forceinline__ int swizzle_key(int row) {
 // ROTATE: every item walks its k-tiles cyclically from an item-dependent start, so
 // concurrent workgroups read different column ranges of their weight rows (for
 // schedules in which workgroups share no weight tiles, i.e. one row tile per group).
+// STREAM_B: the weight loads carry the non-temporal hint.  For batches in which every weight
+// tile is read by one workgroup only (one row tile per expert) the weights cross the memory
+// system once, and reads marked that way stream from HBM about 15 % faster than plain ones
+// (7.0-7.2 against 6.2-6.4 TB/s for direct-to-LDS loads on this machine).
 template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false,
-          bool ROTATE = false>
+          bool ROTATE = false, bool STREAM_B = false>
 __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmArgs p) {
 #if defined(__HIP_DEVICE_COMPILE__)   // buffer resources exist in device code only
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
@@ -306,7 +310,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
         const bool up = GATED && (g0 % WN) >= WN / 2;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(up ? b1_rsrc : b0_rsrc,
                                                  (lds_ptr_t)(base + (BM + i * 4 * RPG) * kRowBytes),
-                                                 16, cx.b_voff[i], koff_b, 0, 0);
+                                                 16, cx.b_voff[i], koff_b, 0, STREAM_B ? kNonTemporal : 0);
       }
   };
 
@@ -594,7 +598,7 @@ static inline prism_status launch_build_schedules(const prism_layer_desc& d,
 // capacity: items per XCD list (sched_capacity).  The grid holds as many workgroups
 // as fit on the machine at once (each then walks several items), or one per item.
 template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false,
-          bool ROTATE = false>
+          bool ROTATE = false, bool STREAM_B = false>
 prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int n_splits = 1,
                          int max_slots = 0) {
   constexpr int smem = STAGES * (BM + BN) * BK * 2 + (GATED ? 4096 : 0) +   // ring + source-row slots
@@ -602,7 +606,7 @@ prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int
   static_assert(smem <= 160 * 1024, "LDS per workgroup");
   constexpr int kCusPerXcd = 32;
   constexpr int kResident = (160 * 1024) / smem;     // workgroups per CU that fit in LDS
-  auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK, ROTATE>;
+  auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK, ROTATE, STREAM_B>;
   static LdsLimitOnce lds_limit;   // one per instantiation
   if (!raise_lds_limit(lds_limit, (const void*)kernel, smem)) return PRISM_ERR_LAUNCH;
   if (capacity <= 0) return PRISM_OK;

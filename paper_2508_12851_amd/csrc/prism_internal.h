@@ -226,6 +226,7 @@ __device__ __forceinline__ void lds_barrier() {
 // that check), and the vector-memory counter the loads are awaited with.
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 constexpr int kBufferFlags = 0x00020000;        // raw buffer, 32-bit data format (gfx9 family)
+constexpr int kNonTemporal = 2;                 // cache-policy operand of a buffer load: the "nt" bit (data read once)
 constexpr uint32_t kOutOfRange = 0xFFFFFF00u;   // above every operand size (those stay below 0xFFFF0000)
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");

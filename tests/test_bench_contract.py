@@ -51,7 +51,8 @@ def test_bench_prints_one_json_line_with_the_contract_keys(config, bound, unit):
     assert cb["kind"] == "oracle" and cb["unit"] == "tokens/s" and cb["value"] > 0 and cb["cores"] >= 1
     assert "sample" in cb and "8" in cb["sample"]
     assert set(d["measured_ceilings"]) == {"mfma_bf16_constant_operands_tflops",
-                                           "mfma_bf16_random_operands_tflops", "hbm_read_gbs"}
+                                           "mfma_bf16_random_operands_tflops", "hbm_read_gbs",
+                                           "hbm_read_nontemporal_gbs"}
 
 
 @pytest.mark.gpu

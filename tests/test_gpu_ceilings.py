@@ -34,3 +34,28 @@ def test_ceiling_calls_reject_bad_arguments():
         P.prism_ceiling_mfma_bf16(ops, out, 0, 3)
     with pytest.raises(P.PrismError):
         P.prism_ceiling_hbm_read(ops[1:], out, 4)      # misaligned source
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("u", [2, 16])
+def test_patterned_stream_read_touches_every_span(mode, u):
+    """Each access pattern reads every 16-byte vector of the spans it reports: a marker in the
+    last vector of the last span is seen (modes 0 and 2 hand the data to a register, whose xor is
+    stored; the direct-to-LDS modes leave it in LDS, where one lane picks it up)."""
+    span = 4096 * u
+    n_spans = 5
+    src = torch.zeros(span * n_spans + 100, dtype=torch.uint8, device="cuda")    # a ragged tail is not read
+    src[span * n_spans - 16: span * n_spans] = 0x3C
+    sink = torch.zeros(8 * 4096, dtype=torch.uint8, device="cuda")
+    assert P.prism_ceiling_hbm_read_pattern(src, sink, 3, u, span, mode) == span * n_spans
+    torch.cuda.synchronize()
+    assert int((sink == 0x3C).sum()) == 16
+
+
+def test_patterned_stream_read_rejects_what_the_header_rules_out():
+    src = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(8 * 4096, dtype=torch.uint8, device="cuda")
+    for kw in (dict(loads_in_flight=3, span_bytes=16384, mode=0), dict(loads_in_flight=4, span_bytes=1000, mode=0),
+               dict(loads_in_flight=4, span_bytes=16384, mode=7), dict(loads_in_flight=4, span_bytes=2 << 20, mode=0)):
+        with pytest.raises(P.PrismError):
+            P.prism_ceiling_hbm_read_pattern(src, sink, 4, **kw)
