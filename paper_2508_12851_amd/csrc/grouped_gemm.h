@@ -450,6 +450,9 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
       const int i = st / kPairs, jp = st % kPairs;
       const int row0 = (i * WGM + wm) * 32;
       const bool live = row0 < cx.row_count;                // wavefront-uniform
+      // keep every strip's instructions together: moved up by the scheduler, the accumulator
+      // reads of all strips would be live at once and push other values into scratch memory
+      __builtin_amdgcn_sched_barrier(0);
       if (live) {
 #pragma unroll
         for (int w8 = 0; w8 < 8; ++w8)
