@@ -147,7 +147,7 @@ prism_status prism_expert_ffn(const prism_layer_desc* desc, const void* x,
   Workspace ws;
   PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
   return launch_expert_ffn(*desc, x, *weights, local_src, local_offsets, T, y, ws.h, ws.tiles,
-                           ws.part, (hipStream_t)stream, nullptr, nullptr);
+                           ws.part, ws.slice_part, (hipStream_t)stream, nullptr, nullptr);
 }
 
 prism_status prism_combine(const prism_layer_desc* desc, const void* y, const int32_t* local_src,
@@ -263,7 +263,7 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                                       ws.local_offsets, remote_src, remote_offsets, n_local_remote,
                                       remote_bytes, ws.inv, ws.route_part, ws.tiles, st, ev));
     PRISM_TRY(launch_expert_ffn(*desc, x, *weights, ws.local_src, ws.local_offsets, T, ws.y, ws.h,
-                                ws.tiles, ws.part, st, ev, &n_splits, true));
+                                ws.tiles, ws.part, ws.slice_part, st, ev, &n_splits, true));
   } else {
     trace(ev, PRISM_STAGE_ROUTE, 0, st);
     // the activation counts come out of the dispatch histogram, not out of the router
@@ -277,7 +277,7 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
                               ws.block_hist, counts, counts_accum, st, ws.tiles, &schedules_built));
     trace(ev, PRISM_STAGE_DISPATCH, 1, st);
     PRISM_TRY(launch_expert_ffn(*desc, x, *weights, ws.local_src, ws.local_offsets, T, ws.y, ws.h,
-                                ws.tiles, ws.part, st, ev, &n_splits, schedules_built));
+                                ws.tiles, ws.part, ws.slice_part, st, ev, &n_splits, schedules_built));
   }
   trace(ev, PRISM_STAGE_COMBINE, 0, st);
   PRISM_TRY(launch_combine(*desc, ws.y, ws.inv, topk_gate, T, out, st, ws.part, n_splits));

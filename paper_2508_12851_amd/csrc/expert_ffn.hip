@@ -146,10 +146,40 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restr
   *reinterpret_cast<bf16x4*>(y + (size_t)row * H + col) = o;
 }
 
+// Adds up the slices of the down-projection tiles whose contraction the schedule cut (its last
+// round of work items): y tile = bf16(sum of the tile's fp32 partial tiles, in slice order).
+// One workgroup per (line of the schedule's list of sliced items, 32 rows of the tile); lines
+// that are not in use end at once.
+constexpr int kSliceTile = 256;    // the partial tiles are 256 x 256 (the prefill tile)
+__global__ __launch_bounds__(256) void sum_slices_kernel(const int32_t* __restrict__ sched, int capacity,
+                                                         const float* __restrict__ part, int N,
+                                                         uint16_t* __restrict__ y) {
+  const int line = blockIdx.x / 8, chunk = blockIdx.x % 8;
+  const int4* red = reinterpret_cast<const int4*>(sched + gg::sched_reduce_offset(capacity)) +
+                    (size_t)line * (gg::kReduceInts / 4);
+  const int n_slices = red[1].x;
+  if (n_slices <= 0) return;
+  const int4 a = red[0];
+  const int row_start = a.x, row_count = a.y, first = a.w;
+  const int row_end = min(row_count, chunk * 32 + 32);
+  const int col0 = a.z * kSliceTile;
+  const int col = (threadIdx.x & 63) * 4;
+  if (col0 + col >= N) return;
+  for (int r = chunk * 32 + (threadIdx.x >> 6); r < row_end; r += 4) {
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < n_slices; ++c)
+      sum += *reinterpret_cast<const f32x4*>(part + ((size_t)(first + c) * kSliceTile + r) * kSliceTile + col);
+    bf16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)sum[e];
+    *reinterpret_cast<bf16x4*>(y + (size_t)(row_start + r) * N + col0 + col) = o;
+  }
+}
+
 template <typename C1, typename C2, bool SPLIT_DOWN, bool STREAM_B = false>
 prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_expert_weights& w,
                           const int32_t* local_src, const int32_t* local_offsets, int T, void* y,
-                          void* h, int32_t* tiles, float* part, hipStream_t st,
+                          void* h, int32_t* tiles, float* part, float* slice_part, hipStream_t st,
                           void* const* stage_events, int* deferred_splits, bool schedules_built) {
   using gg::GemmArgs;
   constexpr bool kRotate = SPLIT_DOWN;   // the decode path: no weight tile is shared between items
@@ -161,8 +191,13 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   int32_t* sched2 = tiles + tile_table_ints(d, T);
   const int nt1 = ceil_div(d.ffn, C1::BN / 2);     // GEMM1 tile: BN/2 gate rows + BN/2 up rows
   const int nt2 = ceil_div(d.hidden, C2::BN);
+  // the down projection's last round of items may be cut along the contraction (prefill only)
+  const int slice_kt = !SPLIT_DOWN && down_slicing_applies(d, T) && slice_part != nullptr ? d.ffn / C2::BK : 0;
+  static_assert(SPLIT_DOWN || (C2::BM == kSliceTile && C2::BN == kSliceTile && C2::BK == 32),
+                "sum_slices_kernel and ffn_schedule_shapes assume the prefill tile");
   if (!schedules_built)
-    PRISM_TRY(gg::launch_build_schedules(d, local_offsets, T, C1::BM, nt1, sched1, C2::BM, nt2, sched2, kRotate, st));
+    PRISM_TRY(gg::launch_build_schedules(d, local_offsets, T, C1::BM, nt1, sched1, C2::BM, nt2, sched2, kRotate,
+                                         slice_kt, st));
 
   GemmArgs g1{};
   g1.A = (const uint16_t*)x;
@@ -183,7 +218,7 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   g2.A = (const uint16_t*)h;
   g2.B0 = w.w_down; g2.B1 = nullptr; g2.SB0 = w.shared_w_down; g2.SB1 = nullptr;
   g2.C = (uint16_t*)y;
-  g2.Cpart = part; g2.c_rows = rows;
+  g2.Cpart = SPLIT_DOWN ? part : slice_part; g2.c_rows = rows;
   g2.sched = sched2; g2.local_src = local_src;
   g2.a_bytes = (uint32_t)((size_t)rows * d.ffn * 2);
   g2.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
@@ -198,6 +233,16 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   trace(stage_events, PRISM_STAGE_FFN_DOWN, 0, st);
   PRISM_TRY((gg::launch_gemm<C2::BM, C2::BN, 2, 2, C2::BK, C2::STAGES, false, SPLIT_DOWN, kRotate, STREAM_B>(
       g2, gg::sched_capacity(d, T, C2::BM, nt2), st, n_splits)));
+  if constexpr (!SPLIT_DOWN) {
+    if (slice_kt > 0)   // the cut last round: one slice entry per workgroup, fp32 partial tiles
+      PRISM_TRY((gg::launch_gemm<C2::BM, C2::BN, 2, 2, C2::BK, C2::STAGES, false, false, false, false, true>(
+          g2, gg::sched_capacity(d, T, C2::BM, nt2), st)));
+  }
+  if (slice_kt > 0) {
+    hipLaunchKernelGGL(sum_slices_kernel, dim3(gg::kXcds * (gg::kSliceSlots / 2) * 8), dim3(256), 0, st, sched2,
+                       gg::sched_capacity(d, T, C2::BM, nt2), slice_part, d.hidden, (uint16_t*)y);
+    PRISM_CHECK_LAUNCH();
+  }
   if (SPLIT_DOWN && deferred_splits != nullptr) {
     *deferred_splits = n_splits;   // the caller's combine sums the slices itself
   } else if (SPLIT_DOWN) {
@@ -215,7 +260,7 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
 prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
-                               int32_t* tiles, float* part, hipStream_t st,
+                               int32_t* tiles, float* part, float* slice_part, hipStream_t st,
                                void* const* stage_events, int* deferred_splits,
                                bool schedules_built) {
   if (deferred_splits != nullptr) *deferred_splits = 0;
@@ -262,12 +307,12 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
     // workgroup, once: the weight loads are marked non-temporal (see STREAM_B).
     if (d.weight_layout == PRISM_WEIGHTS_TILED && d.hidden >= 256 && d.ffn >= 1024)
       return run_bf16_ffn<TileCfg<64, 128, 32, 8>, TileCfg<64, 128, 32, 8>, true, true>(
-          d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
+          d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
     if (d.hidden >= 192 && d.ffn >= 192)
       return run_bf16_ffn<TileCfg<64, 128, 64, 4>, TileCfg<64, 128, 64, 4>, true, true>(
-          d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
+          d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
     return run_bf16_ffn<TileCfg<64, 128, 32, 3>, TileCfg<64, 128, 32, 3>, true, true>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
   }
   // Batches of a few hundred tokens of a wide layer are still bound by streaming the weights
   // once, but an expert now has up to a few hundred rows.  Tiles twice as wide in weight rows
@@ -282,17 +327,17 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
   // layer); beyond, row tiles share weight tiles through the L2 and the hint costs 8-13 %.
   if (stream_tiles_apply(d, T) && T <= 128)
     return run_bf16_ffn<TileCfg<128, 256, 32, 6>, TileCfg<128, 256, 32, 6>, true, true>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
   if (stream_tiles_apply(d, T))
     return run_bf16_ffn<TileCfg<128, 256, 32, 6>, TileCfg<128, 256, 32, 6>, true>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
   // Prefill batch: 256 x 256 tiles (GEMM1: 128 gate + 128 up weight rows).  Very short
   // contractions (H or F of 64) get the shallowest ring.
   if (d.hidden >= 128 && d.ffn >= 128)
     return run_bf16_ffn<TileCfg<256, 256, 32, 4>, TileCfg<256, 256, 32, 4>, false>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
   return run_bf16_ffn<TileCfg<256, 256, 32, 3>, TileCfg<256, 256, 32, 3>, false>(
-      d, x, w, local_src, local_offsets, T, y, h, tiles, part, st, stage_events, deferred_splits, schedules_built);
+      d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
 }
 
 // Batches between the decode and the prefill sizes of layers wide enough for the 6-stage ring,
@@ -302,18 +347,22 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
 // size and run as fast or faster in prefill tiles (measured at E = 60 / 64 with 4 / 2 shared
 // experts: within 3 % up to 256 tokens, 5-18 % faster from 384).
 static bool stream_tiles_apply(const prism_layer_desc& d, int T) {
-  if (T <= kDecodeMaxTokens || T > kStreamMaxTokens || d.hidden < 256 || d.ffn < 1024) return false;
+  const int t_max = slicing_shape(d) ? kStreamMaxTokensSliced : kStreamMaxTokens;
+  if (T <= kDecodeMaxTokens || T > t_max || d.hidden < 256 || d.ffn < 1024) return false;
   const int row_tiles = ceil_div(T * d.top_k, 256) + d.n_experts / 2 + d.n_shared * ceil_div(T, 256);
   return row_tiles * ceil_div(d.hidden, 256) <= 128;
 }
 
-bool ffn_schedule_shapes(const prism_layer_desc& d, int T, int* bm1, int* nt1, int* bm2, int* nt2) {
+bool ffn_schedule_shapes(const prism_layer_desc& d, int T, int* bm1, int* nt1, int* bm2, int* nt2,
+                         int* slice_kt2) {
   const bool stream = stream_tiles_apply(d, T);
   const bool decode = T <= kDecodeMaxTokens;
   // (row tile, weight rows per tile); all ring depths of a path share the tile
   const int bm = stream ? 128 : decode ? 64 : 256, bn = stream ? 256 : decode ? 128 : 256;
   *bm1 = bm; *nt1 = ceil_div(d.ffn, bn / 2);
   *bm2 = bm; *nt2 = ceil_div(d.hidden, bn);
+  // prefill: the down projection's last round may be cut along its contraction (32-wide k-tiles)
+  *slice_kt2 = !decode && !stream && down_slicing_applies(d, T) ? d.ffn / 32 : 0;
   return decode || stream;
 }
 

@@ -116,8 +116,13 @@ template <int BK> __device__ __forceinline__ int swizzle_key(int row) {
 // tile is read by one workgroup only (one row tile per expert) the weights cross the memory
 // system once, and reads marked that way stream from HBM about 15 % faster than plain ones
 // (7.0-7.2 against 6.2-6.4 TB/s for direct-to-LDS loads on this machine).
+// SLICES: the launch takes the schedule's slice entries -- the items of a partly filled last
+// round, cut along the contraction (schedule.h, "Last round") -- instead of its item lists: an
+// entry covers its own range of k-tiles and leaves its accumulators as an fp32 tile in slot
+// `part` of p.Cpart (plain GEMM only).  A launch of its own, so that the kernel that does the
+// bulk of the work carries none of this.
 template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false,
-          bool ROTATE = false, bool STREAM_B = false>
+          bool ROTATE = false, bool STREAM_B = false, bool SLICES = false>
 __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmArgs p) {
 #if defined(__HIP_DEVICE_COMPILE__)   // buffer resources exist in device code only
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
@@ -126,6 +131,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   constexpr int MI = WM / 32, NJ = WN / 32;
   static_assert(MI >= 1 && NJ >= 1 && (!GATED || NJ % 2 == 0), "tile shape");
   static_assert(!(GATED && SPLITK), "the gated epilogue needs complete sums");
+  static_assert(!SLICES || (!GATED && !SPLITK && !ROTATE), "slices are entries of the plain prefill GEMM");
   constexpr int kRowBytes = BK * 2;
   constexpr int CPR = BK / 8;                 // 16-byte chunks per LDS row
   constexpr int RPG = 1024 / kRowBytes;       // rows filled by one wavefront-wide 16-byte load
@@ -148,7 +154,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   const int xcd = blockIdx.x % kXcds;
   const int slot = blockIdx.x / kXcds;
   const const_int_ptr sched_c = (const_int_ptr)p.sched;
-  const int count = sched_c[4 + xcd];
+  const int count = sched_c[(SLICES ? 20 : 4) + xcd];
   if (slot >= count) return;
   // The list takes ceil(count / launched slots) rounds; the fewest workgroups that still
   // finish in that many rounds share it evenly (a workgroup that would sit out the last
@@ -157,8 +163,10 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   const int rounds = (count + launched - 1) / launched;
   const int slots = (count + rounds - 1) / rounds;
   if (slot >= slots) return;
+  // slice entries sit in the last kSliceSlots places of every list
   const const_int4_ptr items =
-      (const_int4_ptr)(p.sched + kSchedHeader) + (size_t)xcd * sched_c[1] * (kItemInts / 4);
+      (const_int4_ptr)(p.sched + kSchedHeader) +
+      ((size_t)xcd * sched_c[1] + (SLICES ? sched_c[1] - kSliceSlots : 0)) * (kItemInts / 4);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -188,10 +196,12 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   // Item header as stored in the schedule.
   struct Item {
     int g, row_start, row_count, tok_base, nt;
+    int kt0, kt_n, part;     // SLICES: the entry's k-tiles [kt0, kt0 + kt_n) and its partial-tile slot
   };
   // What the loads and the epilogue of an item need.
   struct Ctx {
     int row_start, row_count, nt;
+    int kt0, kt_n, part;     // as in Item
     int rot;                 // ROTATE: k-tile this item starts its contraction with
     const void* b0;
     const void* b1;
@@ -202,7 +212,8 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     const int i = min(idx, count - 1);
     const int4 h0 = items[2 * i];
     const int4 h1 = items[2 * i + 1];
-    return Item{h0.x, h0.y, h0.z, h0.w, h1.x};
+    if (SLICES) return Item{h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};
+    return Item{h0.x, h0.y, h0.z, h0.w, h1.x, 0, KT, -1};
   };
   // Second hop: expert pointers (scalar loads) and, for the gathered GEMM, the
   // source rows of the row tile: each wavefront pulls the tile's BM entries of
@@ -248,6 +259,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   auto make_ctx = [&](const Item& it, const Raw& raw) {
     Ctx cx;
     cx.row_start = it.row_start; cx.row_count = it.row_count; cx.nt = it.nt;
+    cx.kt0 = it.kt0; cx.kt_n = it.kt_n; cx.part = it.part;
     cx.rot = ROTATE ? (int)((unsigned)(it.nt * 13 + it.g * 29) % (unsigned)KT) : 0;
     cx.b0 = raw.b0; cx.b1 = raw.b1;
 #pragma unroll
@@ -291,7 +303,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
       kt_mem += cx.rot;
       if (kt_mem >= KT) kt_mem -= KT;
     }
-    const int kel = (kt_first + kt_mem) * BK;                 // first contraction element
+    const int kel = (kt_first + (SLICES ? cx.kt0 : 0) + kt_mem) * BK;   // first contraction element
     const int koff = kel * 2;
     const int koff_b = p.b_tiled ? (kel >> 5) * 1024 : koff;   // kel is a multiple of 32
     const __amdgpu_buffer_rsrc_t b0_rsrc =
@@ -484,6 +496,25 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     }
   };
   auto epilogue = [&](const Ctx& cx) {
+    if constexpr (SLICES) {
+      // the accumulators as they are, an fp32 tile [BM][BN] in slot cx.part
+      float* tile = p.Cpart + (size_t)cx.part * (BM * BN);
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        if ((i * WGM + wm) * 32 >= cx.row_count) continue;    // wave-uniform
+        const int row = (i * WGM + wm) * 32 + r32;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+          for (int vg = 0; vg < 4; ++vg) {
+            const int n = wn * WN + j * 32 + vg * 8 + q * 4;
+            const f32x4 o = {acc[i][j][vg * 4], acc[i][j][vg * 4 + 1], acc[i][j][vg * 4 + 2],
+                             acc[i][j][vg * 4 + 3]};
+            *reinterpret_cast<f32x4*>(tile + (size_t)row * BN + n) = o;
+          }
+      }
+      return;
+    }
     if constexpr (kStagedStore) {
       epilogue_staged(cx);
       return;
@@ -542,7 +573,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
   Item it_next = fetch_item(idx + slots);
 
 #pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) issue_loads(cur, min(s, KT - 1), s, 0, LPS);
+  for (int s = 0; s < STAGES - 1; ++s) issue_loads(cur, min(s, cur.kt_n - 1), s, 0, LPS);
   wait_vmcnt<(STAGES - 2) * LPS>();
   __builtin_amdgcn_s_barrier();
   read_frags(0, 0, 0);
@@ -561,7 +592,8 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // refills still inside this item
-    for (int kt = 0; kt + (STAGES - 1) < KT; ++kt) k_iteration(cur, kt + STAGES - 1);
+    const int kt_n = SLICES ? cur.kt_n : KT;   // (every entry has at least STAGES - 1 k-tiles)
+    for (int kt = 0; kt + (STAGES - 1) < kt_n; ++kt) k_iteration(cur, kt + STAGES - 1);
     // The source rows of the next item were requested before those iterations; loads
     // complete in order, so they have landed once enough younger loads have been
     // waited for, which the iterations above guarantee only if there were enough.
@@ -569,8 +601,8 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     // refills that already belong to the next item (for the last item: a harmless
     // re-fetch of this item's first k-tiles, which keeps the vmcnt bookkeeping uniform)
     const Ctx nxt = make_ctx(it_fill, raw_next);
-    for (int kt = max(KT - (STAGES - 1), 0); kt < KT; ++kt)
-      k_iteration(nxt, min(kt + (STAGES - 1) - KT, KT - 1));
+    for (int kt = max(kt_n - (STAGES - 1), 0); kt < kt_n; ++kt)
+      k_iteration(nxt, min(kt + (STAGES - 1) - kt_n, (SLICES ? nxt.kt_n : KT) - 1));
 
     epilogue(cur);
     if (!has_next) break;
@@ -588,10 +620,10 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
 static inline prism_status launch_build_schedules(const prism_layer_desc& d,
                                                   const int32_t* local_offsets, int T, int bm1,
                                                   int nt1, int32_t* sched1, int bm2, int nt2,
-                                                  int32_t* sched2, bool interleave,
+                                                  int32_t* sched2, bool interleave, int slice_kt2,
                                                   hipStream_t st) {
-  const SchedParams p0{bm1, nt1, sched_capacity(d, T, bm1, nt1), sched1, interleave ? 1 : 0};
-  const SchedParams p1{bm2, nt2, sched_capacity(d, T, bm2, nt2), sched2, interleave ? 1 : 0};
+  const SchedParams p0{bm1, nt1, sched_capacity(d, T, bm1, nt1), sched1, interleave ? 1 : 0, 0};
+  const SchedParams p1{bm2, nt2, sched_capacity(d, T, bm2, nt2), sched2, interleave ? 1 : 0, slice_kt2};
   hipLaunchKernelGGL(build_schedule_kernel, dim3(2), dim3(512), 0, st, local_offsets, d.n_experts,
                      d.n_shared, T, T * d.top_k, p0, p1);
   PRISM_CHECK_LAUNCH();
@@ -601,7 +633,7 @@ static inline prism_status launch_build_schedules(const prism_layer_desc& d,
 // capacity: items per XCD list (sched_capacity).  The grid holds as many workgroups
 // as fit on the machine at once (each then walks several items), or one per item.
 template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false,
-          bool ROTATE = false, bool STREAM_B = false>
+          bool ROTATE = false, bool STREAM_B = false, bool SLICES = false>
 prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int n_splits = 1,
                          int max_slots = 0) {
   constexpr int smem = STAGES * (BM + BN) * BK * 2 + (GATED ? 4096 : 0) +   // ring + source-row slots
@@ -609,7 +641,7 @@ prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int
   static_assert(smem <= 160 * 1024, "LDS per workgroup");
   constexpr int kCusPerXcd = 32;
   constexpr int kResident = (160 * 1024) / smem;     // workgroups per CU that fit in LDS
-  auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK, ROTATE, STREAM_B>;
+  auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK, ROTATE, STREAM_B, SLICES>;
   static LdsLimitOnce lds_limit;   // one per instantiation
   if (!raise_lds_limit(lds_limit, (const void*)kernel, smem)) return PRISM_ERR_LAUNCH;
   if (capacity <= 0) return PRISM_OK;

@@ -46,6 +46,7 @@ struct Workspace {
   void* h;                 // [(A + S*T) * F] layer dtype: silu(gate)*up
   void* y;                 // [(A + S*T) * H] layer dtype: expert outputs
   float* part;             // batches up to kStreamMaxTokens: [kDecodeSplits][A + S*T][H] fp32 partial sums
+  float* slice_part;       // larger batches of wide layers: 256 partial tiles of 256 x 256 fp32 (cut last round of the down projection)
   double* route_part;      // decode batches: [token tiles][kRouteMaxHSplit][route_col_tiles][64][4] fp64
   size_t total;
 };
@@ -60,14 +61,37 @@ static inline int route_col_tiles(int n_experts) {
   return nt;
 }
 
-// ints in one GEMM schedule: a 16-int header, then 8 per-XCD lists of 8-int work items; a list
-// holds at most (row tiles) x ceil(column tiles / 8) items (bounds for the smallest tiles used)
+// ints in one GEMM schedule (schedule.h): a 32-int header, 8 per-XCD lists of 8-int entries -- a
+// list holds at most (row tiles) x ceil(column tiles / 8) items (bounds for the smallest tiles
+// used) plus 32 entries for a last round cut into slices -- and the list of sliced items
+// (8 x 16 lines of 8 ints)
 static inline size_t tile_table_ints(const prism_layer_desc& d, int T) {
   const size_t A = (size_t)T * d.top_k;
   const size_t mt = A / kMinTileM + d.n_experts + (size_t)d.n_shared * ceil_div(T > 0 ? T : 1, kMinTileM) + 1;
   const int wide = d.ffn > d.hidden ? d.ffn : d.hidden;
   const size_t nj8 = ceil_div(ceil_div(wide > 0 ? wide : 1, 64), 8);
-  return align_up(16 + 8 * 8 * mt * nj8, 64);
+  return align_up(32 + 8 * 8 * (mt * nj8 + 32) + 8 * 16 * 8, 64);
+}
+
+// Partial tiles of a down projection whose last round of work items is cut along the contraction:
+// one tile per workgroup.  Prefill batches of layers whose contraction is long enough for the cut
+// to pay: an item of K / 32 k-tiles takes about 0.74 us per k-tile, the cut saves at least half of
+// one item per launch and costs two short launches plus up to 64 MB of fp32 tiles written and read
+// (about 40 us); with fewer than 128 k-tiles (the gate/up GEMM of the same layers included, whose
+// contraction is H) it was measured to lose.
+constexpr int kSliceMinFfn = 4096;
+// With the cut available, prefill tiles beat the 128 x 256 streaming tiles of the mid-size batches
+// earlier (4096 x 14336 layer, 5 of 8 experts hosted: 0.503 against 0.492 ms at 320 tokens, 0.537
+// against 0.556 at 384, 0.564 against 0.629 at 512).
+constexpr int kStreamMaxTokensSliced = 352;
+static inline bool slicing_shape(const prism_layer_desc& d) {
+  return d.dtype == PRISM_BF16 && d.ffn >= kSliceMinFfn && d.hidden >= 128;
+}
+static inline bool down_slicing_applies(const prism_layer_desc& d, int T) {
+  return slicing_shape(d) && T > kStreamMaxTokensSliced;
+}
+static inline size_t slice_part_bytes(const prism_layer_desc& d, int T) {
+  return down_slicing_applies(d, T) ? (size_t)256 * 256 * 256 * 4 : 0;
 }
 
 static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
@@ -94,6 +118,7 @@ static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
   const size_t rows_str = t_str * (size_t)(d.top_k + d.n_shared);
   const bool bf16 = d.dtype == PRISM_BF16;
   w.part = (float*)take(bf16 ? (size_t)kDecodeSplits * rows_str * d.hidden * 4 : 0);
+  w.slice_part = (float*)take(slice_part_bytes(d, T));
   w.route_part = (double*)take(bf16 ? (size_t)ceil_div((int)t_dec, kRouteTokTile) * kRouteMaxHSplit *
                                           route_col_tiles(d.n_experts) * 64 * 4 * 8 : 0);
   w.total = off;
@@ -153,13 +178,14 @@ prism_status launch_dispatch(const prism_layer_desc& d, const int32_t* topk_idx,
                              bool* schedules_built = nullptr);
 
 // schedules_built: the two schedules in tiles already exist (decode front end).
+// slice_part: scratch for a cut last round of the down projection (slice_part_bytes).
 // deferred_splits NULL: y holds the finished expert outputs.  Otherwise the decode path leaves
 // its down projection as *deferred_splits (> 0) fp32 contraction slices in part, y unwritten,
 // for launch_combine to sum; *deferred_splits == 0 means y is finished.
 prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
-                               int32_t* tiles, float* part, hipStream_t st,
+                               int32_t* tiles, float* part, float* slice_part, hipStream_t st,
                                void* const* stage_events, int* deferred_splits,
                                bool schedules_built = false);
 
@@ -179,9 +205,11 @@ prism_status launch_decode_front_end(const prism_layer_desc& d, const void* x, c
                                      int32_t* tiles, hipStream_t st, void* const* stage_events);
 
 // Tile shapes of the two grouped GEMMs of launch_expert_ffn for a bf16 batch of T tokens (row
-// tile, column tiles), which whoever builds their schedules needs; returns whether the
-// schedules deal their items to the XCDs one by one (decode batches).
-bool ffn_schedule_shapes(const prism_layer_desc& d, int T, int* bm1, int* nt1, int* bm2, int* nt2);
+// tile, column tiles), which whoever builds their schedules needs, and the k-tiles of the down
+// projection's contraction if the schedule may cut its last round along it (else 0); returns
+// whether the schedules deal their items to the XCDs one by one (decode batches).
+bool ffn_schedule_shapes(const prism_layer_desc& d, int T, int* bm1, int* nt1, int* bm2, int* nt2,
+                         int* slice_kt2);
 
 // Records stage_events[2 * stage + end] on st when tracing is on and the pair is set.
 static inline void trace(void* const* ev, int stage, int end, hipStream_t st) {

@@ -10,17 +10,34 @@ namespace gg {
 
 constexpr int kMaxGroups = PRISM_MAX_EXPERTS + PRISM_MAX_SHARED;
 constexpr int kXcds = 8;
-constexpr int kSchedHeader = 16;     // ints
+constexpr int kSchedHeader = 32;     // ints
 constexpr int kItemInts = 8;         // ints per work item
+constexpr int kMaxSlices = 16;       // contraction slices of one sliced item, at most
+constexpr int kMinSliceKt = 8;       // k-tiles of one slice, at least
+constexpr int kSliceSlots = 32;      // workgroups per XCD that sliced lists are cut for
+constexpr int kReduceInts = 8;       // ints per entry of the list of sliced items
 
 // Schedule memory (int32):
-//   [0] n_mtiles  [1] capacity of one XCD list (items)  [4 + x] items in the list of XCD x
-//   then, from int kSchedHeader on, 8 lists of `capacity` items of 8 ints:
+//   [0] n_mtiles  [1] capacity of one XCD list (entries)  [4 + x] items in the list of XCD x
+//   [20 + x] slice entries of XCD x (they occupy the last kSliceSlots places of its list)
+//   then, from int kSchedHeader on, 8 lists of `capacity` entries of 8 ints:
 //     [0] group id g (g < E: routed expert g; else shared expert g - E)
 //     [1] first row of the row tile in h / y row space
 //     [2] rows in the tile (1..BM)
 //     [3] first token of the tile for shared experts, -1 for routed ones
 //     [4] column tile
+//     slice entries only: [5] first k-tile, [6] number of k-tiles, [7] slot of the fp32
+//     partial tile the entry writes
+//   then 8 x kSliceSlots / 2 entries of 8 ints, the sliced items for the kernel that sums their
+//   slices: [0] first row [1] rows [2] column tile [3] first partial slot [4] slices (0: unused)
+//
+// Last round.  With n items on w workgroups an XCD needs ceil(n / w) rounds, and the last one
+// keeps only n mod w workgroups busy for a whole item.  If the caller allows it (slice_kt),
+// the items of that round are cut along the contraction into s = floor(w / (n mod w)) slices
+// (at most kMaxSlices, each at least kMinSliceKt k-tiles), which are entries of their own:
+// the last round then takes 1 / s of an item.  The slice entries are run by a launch of their
+// own (one entry per workgroup), each leaving its accumulators as an fp32 partial tile; a
+// small kernel adds the slices of a tile in slice order afterwards.
 //
 // Work order.  The (row tile, column tile) grid of every group is cut into rectangles of
 // about kRectRows x kRectCols tiles (a group's row tiles and the column tiles are split
@@ -43,7 +60,14 @@ struct SchedParams {
   int interleave;    // 1: deal the sequence to the XCDs item by item instead of in eighths
                      // (schedules whose items share nothing: every XCD then reads from all
                      // parts of the weight matrices at any time)
+  int slice_kt;      // k-tiles of the contraction if the items of a partly filled last round may be
+                     // cut along it (the launch then has kSliceSlots workgroups per XCD); else 0
 };
+
+// Where the list of sliced items starts (ints from the start of the schedule).
+__host__ __device__ inline size_t sched_reduce_offset(int capacity) {
+  return (size_t)kSchedHeader + (size_t)kXcds * capacity * kItemInts;
+}
 
 // Equal split of `count` things into the fewest parts of at most `part_max`: which part
 // holds element i, where that part starts and how long it is.
@@ -60,6 +84,19 @@ __device__ __forceinline__ PartOf part_of(int i, int count, int part_max) {
   }
   const int q = (i - split) / base;
   return PartOf{split + q * base, base};
+}
+
+// How the last round of an XCD list of n items is cut: its `items` items into `slices` entries
+// each (slices == 0: not cut).
+struct Slicing {
+  int items, slices;
+};
+__device__ __forceinline__ Slicing slicing_of(int n, int slice_kt) {
+  const int left = n % kSliceSlots;
+  if (slice_kt <= 0 || left == 0) return Slicing{0, 0};
+  int s = kSliceSlots / left;
+  s = min(s, min(kMaxSlices, slice_kt / kMinSliceKt));
+  return s >= 2 ? Slicing{left, s} : Slicing{0, 0};
 }
 
 // Builds NS (1 or 2) schedules of the same row groups side by side; called by every
@@ -114,7 +151,9 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
         count = total > x ? (total - x + kXcds - 1) / kXcds : 0;
       else                 // every list holds per_xcd items, the last non-empty one the remainder
         count = total > x * per_xcd ? min(per_xcd, total - x * per_xcd) : 0;
-      ps.sched[4 + x] = (int)count;
+      const Slicing sl = slicing_of((int)count, ps.slice_kt);
+      ps.sched[4 + x] = (int)count - sl.items;
+      ps.sched[20 + x] = sl.items * sl.slices;
     }
   }
   lds_barrier();
@@ -146,11 +185,42 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
                            (unsigned)(rp.len * cp.first + (nt - cp.first) * rp.len + (mi - rp.first));
       const unsigned x = interleave ? seq % kXcds : seq / per_xcd;
       const unsigned pos = interleave ? seq / kXcds : seq - x * per_xcd;
-      int4* out = reinterpret_cast<int4*>(p[s].sched + kSchedHeader +
-                                          ((size_t)x * capacity + pos) * kItemInts);
-      out[0] = int4{g, s_row0[g] + mi * BM, min(BM, s_rows[g] - mi * BM), g < E ? -1 : mi * BM};
-      out[1] = int4{nt, 0, 0, 0};
+      const int4 head = int4{g, s_row0[g] + mi * BM, min(BM, s_rows[g] - mi * BM), g < E ? -1 : mi * BM};
+      int4* list = reinterpret_cast<int4*>(p[s].sched + kSchedHeader + (size_t)x * capacity * kItemInts);
+      const unsigned in_list = interleave ? 0u : (n_items > x * per_xcd ? min(per_xcd, n_items - x * per_xcd) : 0u);
+      const Slicing sl = slicing_of((int)in_list, interleave ? 0 : p[s].slice_kt);
+      const int first_sliced = (int)in_list - sl.items;
+      if ((int)pos < first_sliced || sl.slices == 0) {
+        list[2 * pos] = head;
+        list[2 * pos + 1] = int4{nt, 0, 0, 0};
+      } else {
+        // the li-th item of the last round: sl.slices entries, slice after slice, and its line
+        // in the list of sliced items
+        const int li = (int)pos - first_sliced;
+        const int kt_all = p[s].slice_kt;
+        for (int c = 0; c < sl.slices; ++c) {
+          const int e = capacity - kSliceSlots + li * sl.slices + c;
+          const int k0 = (int)((long long)kt_all * c / sl.slices), k1 = (int)((long long)kt_all * (c + 1) / sl.slices);
+          list[2 * e] = head;
+          list[2 * e + 1] = int4{nt, k0, k1 - k0, (int)x * kSliceSlots + li * sl.slices + c};
+        }
+        int4* red = reinterpret_cast<int4*>(p[s].sched + sched_reduce_offset(capacity)) +
+                    ((size_t)x * (kSliceSlots / 2) + li) * (kReduceInts / 4);
+        red[0] = int4{head.y, head.z, nt, (int)x * kSliceSlots + li * sl.slices};
+        red[1] = int4{sl.slices, 0, 0, 0};
+      }
     }
+    // lines of the list of sliced items that this call does not use are marked empty
+    if (!interleave && p[s].slice_kt > 0)
+      for (int r = part * blockDim.x + threadIdx.x; r < kXcds * (kSliceSlots / 2); r += n_parts * blockDim.x) {
+        const unsigned x = (unsigned)r / (kSliceSlots / 2);
+        const int li = r % (kSliceSlots / 2);
+        const unsigned in_list = n_items > x * per_xcd ? min(per_xcd, n_items - x * per_xcd) : 0u;
+        const Slicing sl = slicing_of((int)in_list, p[s].slice_kt);
+        if (li >= sl.items || sl.slices == 0)
+          reinterpret_cast<int4*>(p[s].sched + sched_reduce_offset(capacity))[(size_t)r * (kReduceInts / 4) + 1] =
+              int4{0, 0, 0, 0};
+      }
   }
 }
 
@@ -159,9 +229,10 @@ static inline int max_row_tiles(const prism_layer_desc& d, int T, int BM) {
   return T * d.top_k / BM + d.n_experts + d.n_shared * ceil_div(T, BM);
 }
 
-// Items one XCD list must be able to hold: every row tile times its share of the column tiles.
+// Entries one XCD list must be able to hold: every row tile times its share of the column
+// tiles, plus the slices a cut last round adds (at most one entry per workgroup).
 static inline int sched_capacity(const prism_layer_desc& d, int T, int BM, int n_ntiles) {
-  return max_row_tiles(d, T, BM) * ceil_div(n_ntiles, kXcds);
+  return max_row_tiles(d, T, BM) * ceil_div(n_ntiles, kXcds) + kSliceSlots;
 }
 
 }  // namespace gg

@@ -200,3 +200,20 @@ def test_expert_ffn_with_local_src_at_the_very_end_of_its_allocation(T, S):
                          d.local_offsets, cfg.k)
     got = to_f32(y_tail)
     assert rel_err(np.concatenate([got[:d.n_local], got[A:]]), y_ref) <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("T,H,F,E,n_local", [(513, 128, 4096, 8, 5), (700, 256, 4160, 8, 5), (1100, 512, 4096, 4, 3),
+                                               (2300, 256, 4096, 2, 2), (900, 768, 5120, 16, 9),
+                                               (600, 256, 4032, 8, 5)])
+def test_prefill_batches_whose_last_round_of_the_down_projection_is_cut(T, H, F, E, n_local):
+    """More than 512 tokens of a layer with a long down-projection contraction (F >= 4096; the last
+    case is just below and takes the plain path): the
+    items of the partly filled last round are cut along the contraction into slice entries, run
+    by a launch of their own and summed in slice order.  Row-major and tiled weights."""
+    cfg = make_config("cfg2_mixtral_prefill", T=T, H=H, F=F, E=E, k=2, n_local=n_local)
+    inp = make_inputs(cfg)
+    ref = oracle_layer(inp)
+    for tiled in (False, True):
+        o = run_layer(cfg, inp, wt=weight_table(inp, tiled=tiled), weight_layout="tiled" if tiled else "row_major")
+        err = check_layer(cfg, o, ref)
+        print(f"T={T} H={H} F={F} tiled={tiled}: out err {err:.3g}")
