@@ -96,8 +96,12 @@ def _is_gated(k):
 
 
 def _is_plain(k):
+    """The down projection's main launch (not the launch for the slices of a cut last round)."""
     m = re.search(r"grouped_gemm_kernel<([^>]*)>", k)
-    return bool(m) and m.group(1).split(",")[6].strip() == "false"
+    if not m:
+        return False
+    a = [t.strip() for t in m.group(1).split(",")]
+    return a[6] == "false" and (len(a) < 11 or a[10] == "false")
 
 
 def traffic(base, workload, bench_args):
