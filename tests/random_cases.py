@@ -40,3 +40,22 @@ def draw_case(i):
                 n_swapped=0, bias_group_tokens=pick([0, 0, 16, 64, 128]), mask_kind=pick(["top", "random"]),
                 zipf_s=pick([0.0, 1.0, 1.2]), seed=100 + i), \
         pick(["renormalized", "softmax_all"]), (not f32) and H % 32 == 0 and F % 32 == 0 and bool(rng.integers(0, 2))
+
+
+def draw_wide_case(i):
+    """Random prefill batches of layers with a long down-projection contraction (F >= 4096), where
+    the schedule cuts a partly filled last round of work items into slices: few experts, so that
+    the number of row tiles -- and with it the number of items left over -- varies from case to case."""
+    rng = np.random.default_rng(9000 + i)
+    pick = lambda seq: seq[int(rng.integers(0, len(seq)))]
+    E = pick([2, 3, 4, 6, 8])
+    k = int(rng.integers(1, min(3, E) + 1))
+    S = pick([0, 0, 1])
+    H, F = pick([128, 256, 512]), pick([4096, 4160, 4608, 5120])
+    T = int(rng.integers(353, 2600))
+    while T * (k + S) * H * F > 3e9 and T > 353:
+        T = max(353, T * 3 // 4)
+    n_local = int(pick([E, E, max(1, E - 1), int(rng.integers(1, E + 1))]))
+    return dict(dtype="bf16", T=T, H=H, F=F, E=E, k=k, S=S, n_local=n_local, n_swapped=0,
+                bias_group_tokens=pick([0, 0, 256]), mask_kind=pick(["top", "random"]),
+                zipf_s=pick([0.0, 1.0]), seed=300 + i), bool(rng.integers(0, 2))

@@ -103,3 +103,18 @@ def test_separate_calls_parity_on_a_random_shape(i):
         err = rel_err(to_f32(out), done_ref)
         assert err <= 1.5 * TOL[cfg.dtype], err                   # one more bf16 rounding on the way
     print(f"case {i}: n_local {nl}, n_remote {nr}: all stages agree")
+
+
+@pytest.mark.parametrize("i", range(12))
+def test_layer_parity_on_a_random_wide_shape(i):
+    """Prefill batches whose down projection may have its last round of items cut along the
+    contraction (F >= 4096): whole layer against the oracle, whole-batch error measure."""
+    from random_cases import draw_wide_case
+    kw, tiled = draw_wide_case(i)
+    print(f"wide case {i}: {kw} tiled={tiled}", flush=True)
+    cfg = make_config("cfg2_mixtral_prefill", **kw)
+    inp = make_inputs(cfg)
+    ref = oracle_layer(inp)
+    o = run_layer(cfg, inp, wt=weight_table(inp, tiled=tiled), weight_layout="tiled" if tiled else "row_major")
+    err = check_layer(cfg, o, ref)
+    print(f"wide case {i}: out err {err:.3g}, n_local {ref.dispatch.n_local}, n_remote {ref.dispatch.n_remote}")
