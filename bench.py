@@ -123,8 +123,8 @@ class DeviceWeights:
     """Expert weights uploaded once per (expert, layout) and shared by the workloads of a run
     that use the same layer (the decode batch runs on the prefill batch's layer)."""
 
-    def __init__(self, torch, P, layout):
-        self.torch, self.P, self.layout = torch, P, layout
+    def __init__(self, torch, P, layout, values="real"):
+        self.torch, self.P, self.layout, self.values = torch, P, layout, values
         self.cache = {}
 
     def dev(self, a):
@@ -136,7 +136,12 @@ class DeviceWeights:
     def triple(self, key, arrays):
         if key not in self.cache:
             up = (lambda a: self.P.prism_pack_weights(self.dev(a))) if self.layout == "tiled" else self.dev
-            self.cache[key] = tuple(up(w) for w in arrays)
+            t = tuple(up(w) for w in arrays)
+            if self.values == "zero":
+                t = tuple(w.zero_() for w in t)
+            elif self.values == "constant":
+                t = tuple(w.fill_(2.0 ** -6) for w in t)
+            self.cache[key] = t
         return self.cache[key]
 
 
@@ -222,7 +227,8 @@ def run_workload(torch, P, cfg, inp, args, dw, *, steps, warmup, decode, label, 
     dom_ms = stage_ms["ffn_up"]
     step_s = ms_per_step * 1e-3
     # the committed counter summaries were taken on the benchmark workloads as bench.py runs them by default
-    as_profiled = label == cfg.name and args.mask == "top" and args.weight_layout == "tiled"
+    as_profiled = (label == cfg.name and args.mask == "top" and args.weight_layout == "tiled" and
+                   args.expert_weights == "real")
     traffic, traffic_note = read_traffic(cfg.name) if as_profiled else (None, "not the profiled workload")
     if decode:
         # the dominant kernel streams W_gate and W_up of every hosted expert that received a token
@@ -303,6 +309,11 @@ def main():
     ap.add_argument("--tokens", type=int, default=None,
                     help="another batch size for the chosen workload's layer (not the benchmark line: "
                          "config.workload then says so)")
+    ap.add_argument("--expert-weights", choices=("real", "zero", "constant"), default="real",
+                    help="a measurement, not the benchmark line: overwrite the expert weights in HBM with zeros or "
+                         "with one constant after loading them -- same routing, same kernels, same memory traffic, "
+                         "but operands that barely toggle the matrix cores, which shows how much of the GEMM time "
+                         "is the chip's data-dependent, power-limited clock")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the measured MFMA / HBM ceilings of this GPU")
     args = ap.parse_args()
@@ -335,7 +346,9 @@ def main():
     warmup = args.warmup if args.warmup is not None else (20 if decode else 5)
     phases = [0] if cfg.n_phases == 1 else ([0, 1] if args.phase == "both" else [int(args.phase)])
 
-    dw = DeviceWeights(torch, P, args.weight_layout)
+    dw = DeviceWeights(torch, P, args.weight_layout, args.expert_weights)
+    if args.expert_weights != "real":
+        workload += f" with {args.expert_weights} expert weights (a power measurement, not the benchmark)"
     recs, inputs = [], []
     for phase in phases:
         t0 = time.perf_counter()
