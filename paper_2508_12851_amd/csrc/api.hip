@@ -189,7 +189,7 @@ prism_status prism_combine_remote(const prism_layer_desc* desc, const void* y_re
   PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
   const hipStream_t st = (hipStream_t)stream;
   PRISM_TRY(launch_build_inverse(*desc, remote_src, remote_offsets, T, ws.inv, st));
-  return launch_combine(*desc, y_remote, ws.inv, topk_gate, T, out, st, nullptr, 0, true);
+  return launch_combine(*desc, y_remote, ws.inv, topk_gate, T, out, st, nullptr, nullptr, true);
 }
 
 prism_status prism_pack_weights(const void* src, int32_t rows, int32_t cols, void* dst, void* stream) {
@@ -256,7 +256,7 @@ prism_status prism_moe_layer_traced(const prism_layer_desc* desc, const void* x,
   PRISM_TRY(check_workspace(*desc, T, workspace, workspace_bytes, &ws));
   const hipStream_t st = (hipStream_t)stream;
   void* const* ev = stage_events;
-  int n_splits = 0;
+  const int32_t* n_splits = nullptr;   // set if the down projection is left as contraction slices
   if (decode_front_end_applies(*desc, T)) {
     PRISM_TRY(launch_decode_front_end(*desc, x, w_router, router_bias, local_mask, T, topk_idx,
                                       topk_gate, counts, counts_accum, ws.local_src,

@@ -154,7 +154,7 @@ __device__ __forceinline__ f32x4 sum_slices(const SliceRow& r, int n_splits) {
 }
 
 __global__ __launch_bounds__(256) void combine_slices_kernel(const float* __restrict__ part,
-                                                             int n_splits,
+                                                             const int32_t* __restrict__ n_splits_ptr,
                                                              const int32_t* __restrict__ inv,
                                                              const float* __restrict__ gate, int T,
                                                              int H, int k, int S,
@@ -166,6 +166,7 @@ __global__ __launch_bounds__(256) void combine_slices_kernel(const float* __rest
   const int col = (int)(gid - (long long)t * vec_per_row) * 4;
   const size_t A = (size_t)T * k;
   const size_t rows = A + (size_t)S * T;
+  const int n_splits = min(*n_splits_ptr, kDecodeSplits);   // what the schedule builder chose
   int row_of[PRISM_MAX_TOPK];
   float gate_of[PRISM_MAX_TOPK];
 #pragma unroll
@@ -245,10 +246,10 @@ prism_status launch_pack_rows(const prism_layer_desc& d, const void* x, const in
 
 prism_status launch_combine(const prism_layer_desc& d, const void* y, const int32_t* inv,
                             const float* topk_gate, int T, void* out, hipStream_t st,
-                            const float* part, int n_splits, bool add_to_out) {
+                            const float* part, const int32_t* n_splits, bool add_to_out) {
   if (T == 0) return PRISM_OK;
   if (add_to_out) {   // returned remote rows: no shared experts, no slices
-    if (n_splits > 0) return PRISM_ERR_INVALID_ARG;
+    if (n_splits != nullptr) return PRISM_ERR_INVALID_ARG;
     const int nv = d.dtype == PRISM_F32 ? 4 : 8;
     const long long th = (long long)T * (d.hidden / nv);
     const unsigned bl = (unsigned)((th + 255) / 256);
@@ -261,9 +262,8 @@ prism_status launch_combine(const prism_layer_desc& d, const void* y, const int3
     PRISM_CHECK_LAUNCH();
     return PRISM_OK;
   }
-  if (n_splits > 0 && (d.dtype != PRISM_BF16 || part == nullptr || n_splits > kDecodeSplits))
-    return PRISM_ERR_INVALID_ARG;
-  if (n_splits > 0) {
+  if (n_splits != nullptr && (d.dtype != PRISM_BF16 || part == nullptr)) return PRISM_ERR_INVALID_ARG;
+  if (n_splits != nullptr) {
     const long long threads = (long long)T * (d.hidden / 4);
     hipLaunchKernelGGL(combine_slices_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0,
                        st, part, n_splits, inv, topk_gate, T, d.hidden, d.top_k, d.n_shared,

@@ -100,11 +100,7 @@ prism_status launch_dispatch(const prism_layer_desc& d, const int32_t* topk_idx,
   const int n_blocks = ceil_div(A, sub * kDispatchChunk);
   int n_sched = 0;
   if (tiles != nullptr && d.dtype == PRISM_BF16) {
-    int bm1, nt1, bm2, nt2, slice_kt2;
-    const bool interleave = ffn_schedule_shapes(d, T, &bm1, &nt1, &bm2, &nt2, &slice_kt2);
-    p0 = gg::SchedParams{bm1, nt1, gg::sched_capacity(d, T, bm1, nt1), tiles, interleave ? 1 : 0, 0};
-    p1 = gg::SchedParams{bm2, nt2, gg::sched_capacity(d, T, bm2, nt2), tiles + tile_table_ints(d, T),
-                         interleave ? 1 : 0, slice_kt2};
+    gg::ffn_sched_params(d, T, tiles, &p0, &p1);
     n_sched = 2 * kSchedParts;
     if (schedules_built != nullptr) *schedules_built = true;
   }

@@ -126,11 +126,41 @@ template <int BM_, int BN_, int BK_, int STAGES_> struct TileCfg {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_;
 };
 
+// Fixed cost of one round of items of a split down projection, as weight bytes a workgroup
+// could have streamed meanwhile (first loads of the ring, epilogue, partial-tile stores): fitted
+// to the times of a 32-token batch of the 4096 x 14336 layer run with 2 to 8 splits.
+constexpr float kSplitRoundBytes = 14 * 8192.f;
+
+// What the schedule builders need to know about a path's two GEMMs (C1: gate/up, C2: down).
+template <typename C1, typename C2, bool SPLIT_DOWN>
+FfnShapes shapes_of(const prism_layer_desc& d, int T) {
+  FfnShapes f{};
+  f.bm1 = C1::BM;
+  f.nt1 = ceil_div(d.ffn, C1::BN / 2);     // GEMM1 tile: BN/2 gate rows + BN/2 up rows
+  f.bm2 = C2::BM;
+  f.nt2 = ceil_div(d.hidden, C2::BN);
+  f.interleave = SPLIT_DOWN;               // the paths that stream the weights once
+  // prefill tiles: the down projection's last round may be cut along its contraction
+  f.slice_kt2 = !SPLIT_DOWN && C2::BM == 256 && down_slicing_applies(d, T) ? d.ffn / C2::BK : 0;
+  if (SPLIT_DOWN) {
+    f.split_kt2 = d.ffn / C2::BK;
+    f.split_min_kt2 = C2::STAGES - 1;      // a slice must be at least as long as the k-tile ring
+    f.split_wgs2 = gg::gemm_wgs_per_xcd<C2::BM, C2::BN, 2, C2::BK, C2::STAGES, false, true>();
+    const float kt_bytes = (float)(C2::BN * C2::BK * 2);   // weight bytes of one k-tile
+    f.split_round_kt2 = kSplitRoundBytes / kt_bytes;
+    // one more split: every row written once more as fp32 and read once more, shared by all workgroups
+    f.split_row_kt2 = (float)d.hidden * 8.f / (float)(gg::kXcds * f.split_wgs2) / kt_bytes;
+  }
+  return f;
+}
+
 // Sums the contraction slices of the split down projection: y = bf16(sum_s part[s]).
 __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part,
                                                             const int32_t* __restrict__ local_offsets,
-                                                            int E, int A, int rows, int H, int n_splits,
+                                                            int E, int A, int rows, int H,
+                                                            const int32_t* __restrict__ n_splits_ptr,
                                                             uint16_t* __restrict__ y) {
+  const int n_splits = *n_splits_ptr;   // what the schedule builder chose
   const int vec_per_row = H / 4;
   const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= (long long)rows * vec_per_row) return;
@@ -180,7 +210,8 @@ template <typename C1, typename C2, bool SPLIT_DOWN, bool STREAM_B = false>
 prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_expert_weights& w,
                           const int32_t* local_src, const int32_t* local_offsets, int T, void* y,
                           void* h, int32_t* tiles, float* part, float* slice_part, hipStream_t st,
-                          void* const* stage_events, int* deferred_splits, bool schedules_built) {
+                          void* const* stage_events, const int32_t** deferred_splits,
+                          bool schedules_built) {
   using gg::GemmArgs;
   constexpr bool kRotate = SPLIT_DOWN;   // the decode path: no weight tile is shared between items
   const int A = T * d.top_k;
@@ -189,15 +220,21 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   if (d.hidden / C1::BK < C1::STAGES - 1 || d.ffn / C2::BK < C2::STAGES - 1) return PRISM_ERR_UNSUPPORTED;
   int32_t* sched1 = tiles;
   int32_t* sched2 = tiles + tile_table_ints(d, T);
-  const int nt1 = ceil_div(d.ffn, C1::BN / 2);     // GEMM1 tile: BN/2 gate rows + BN/2 up rows
-  const int nt2 = ceil_div(d.hidden, C2::BN);
+  // The schedules (built here, or by the caller's dispatch) follow ffn_schedule_shapes(), which
+  // must describe the kernels this instantiation launches.
+  const FfnShapes f = shapes_of<C1, C2, SPLIT_DOWN>(d, T);
+  const FfnShapes told = ffn_schedule_shapes(d, T);
+  if (f.bm1 != told.bm1 || f.nt1 != told.nt1 || f.bm2 != told.bm2 || f.nt2 != told.nt2 ||
+      f.interleave != told.interleave || f.slice_kt2 != told.slice_kt2 || f.split_kt2 != told.split_kt2 ||
+      f.split_wgs2 != told.split_wgs2)
+    return PRISM_ERR_LAUNCH;
+  const int nt1 = f.nt1, nt2 = f.nt2;
   // the down projection's last round of items may be cut along the contraction (prefill only)
-  const int slice_kt = !SPLIT_DOWN && down_slicing_applies(d, T) && slice_part != nullptr ? d.ffn / C2::BK : 0;
+  const int slice_kt = slice_part != nullptr ? f.slice_kt2 : 0;
+  if (slice_kt != f.slice_kt2) return PRISM_ERR_INVALID_ARG;   // the schedule would hold slice entries
   static_assert(SPLIT_DOWN || (C2::BM == kSliceTile && C2::BN == kSliceTile && C2::BK == 32),
-                "sum_slices_kernel and ffn_schedule_shapes assume the prefill tile");
-  if (!schedules_built)
-    PRISM_TRY(gg::launch_build_schedules(d, local_offsets, T, C1::BM, nt1, sched1, C2::BM, nt2, sched2, kRotate,
-                                         slice_kt, st));
+                "sum_slices_kernel assumes the prefill tile");
+  if (!schedules_built) PRISM_TRY(gg::launch_build_schedules(d, local_offsets, T, tiles, st));
 
   GemmArgs g1{};
   g1.A = (const uint16_t*)x;
@@ -224,15 +261,11 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   g2.b_bytes = (uint32_t)((size_t)d.ffn * d.hidden * 2);
   g2.K = d.ffn; g2.N = d.hidden; g2.top_k = d.top_k; g2.E = d.n_experts;
   g2.b_tiled = d.weight_layout == PRISM_WEIGHTS_TILED;
-  // every contraction slice must be at least as long as the k-tile ring
-  int n_splits = 1;
-  if (SPLIT_DOWN) {
-    n_splits = (d.ffn / C2::BK) / (C2::STAGES - 1);
-    if (n_splits > kDecodeSplits) n_splits = kDecodeSplits;
-  }
+  // SPLIT_DOWN: the number of contraction slices is in the schedule's header (schedule.h, "Splits")
+  const int32_t* n_splits = sched2 + 2;
   trace(stage_events, PRISM_STAGE_FFN_DOWN, 0, st);
   PRISM_TRY((gg::launch_gemm<C2::BM, C2::BN, 2, 2, C2::BK, C2::STAGES, false, SPLIT_DOWN, kRotate, STREAM_B>(
-      g2, gg::sched_capacity(d, T, C2::BM, nt2), st, n_splits)));
+      g2, gg::sched_capacity(d, T, C2::BM, nt2), st)));
   if constexpr (!SPLIT_DOWN) {
     if (slice_kt > 0)   // the cut last round: one slice entry per workgroup, fp32 partial tiles
       PRISM_TRY((gg::launch_gemm<C2::BM, C2::BN, 2, 2, C2::BK, C2::STAGES, false, false, false, false, true>(
@@ -255,15 +288,69 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
   return PRISM_OK;
 }
 
+// One tile path of the bf16 FFN: tile shapes of the two GEMMs, whether the down projection is
+// split along its contraction, whether the weight loads are marked non-temporal.
+template <typename C1_, typename C2_, bool SPLIT_DOWN_, bool STREAM_B_> struct Path {
+  using C1 = C1_;
+  using C2 = C2_;
+  static constexpr bool kSplitDown = SPLIT_DOWN_, kStreamB = STREAM_B_;
+};
+
+// Calls fn(Path<...>{}) with the path that serves a bf16 batch of T tokens of layer d.
+template <typename Fn>
+auto select_path(const prism_layer_desc& d, int T, Fn&& fn) {
+  if (T <= kDecodeMaxTokens) {
+    // Decode batch: every expert has at most 64 rows, the layer is bound by streaming
+    // the weights once.  Small tiles make ~1000 work items; the down projection also
+    // splits its contraction (the slices are summed by a last kernel or by the combine).
+    // No weight tile is shared between workgroups here, so every item starts its
+    // contraction at a different k-tile: at any moment the workgroups then read
+    // different column ranges of the weight rows, whose power-of-two pitch would
+    // otherwise send them all to the same few memory channels.
+    // Tiled weights: 32-wide k-tiles, so that one load instruction takes one whole 1 KiB
+    // tile (with 64-wide k-tiles it would take halves of two), and twice the stages.
+    // An expert has one row tile here, so every weight element is read by exactly one
+    // workgroup, once: the weight loads are marked non-temporal (see STREAM_B).
+    if (d.weight_layout == PRISM_WEIGHTS_TILED && d.hidden >= 256 && d.ffn >= 1024)
+      return fn(Path<TileCfg<64, 128, 32, 8>, TileCfg<64, 128, 32, 8>, true, true>{});
+    if (d.hidden >= 192 && d.ffn >= 192)
+      return fn(Path<TileCfg<64, 128, 64, 4>, TileCfg<64, 128, 64, 4>, true, true>{});
+    return fn(Path<TileCfg<64, 128, 32, 3>, TileCfg<64, 128, 32, 3>, true, true>{});
+  }
+  // Batches of a few hundred tokens of a wide layer are still bound by streaming the weights
+  // once, but an expert now has up to a few hundred rows; the down projection splits its
+  // contraction as for decode batches.
+  // Up to 128 tokens an expert still has a single row tile of 128 (a token picks an expert at
+  // most once), so the weights are read once and stream.  128 x 128 tiles with 64-wide k-tiles
+  // there (4096 x 14336 layer, 5 of 8 experts hosted, 128 tokens: 0.388 ms against 0.418 with
+  // the tiles of the next case; at 256 tokens they lose, 0.471 against 0.466).
+  if (stream_tiles_apply(d, T) && T <= kMidMaxTokens)
+    return fn(Path<TileCfg<128, 128, 64, 4>, TileCfg<128, 128, 64, 4>, true, true>{});
+  // Beyond, row tiles share weight tiles through the L2 and the non-temporal hint costs 8-13 %.
+  // Tiles twice as wide in weight rows (256) as in activation rows (128) bring twice the HBM
+  // bytes per k-tile for the same waits and barriers, and the padding rows of a half-empty
+  // 256-row tile would cost their loads and MFMAs like real ones.  (256 x 128 tiles: 0.50 ms
+  // for 256 tokens of the 4096 x 14336 layer with 5 of 8 experts hosted; 128 x 256: 0.43 ms;
+  // the 256 x 256 prefill tiles: 0.62 ms, their down projection has too few items to fill the
+  // machine.)
+  if (stream_tiles_apply(d, T))
+    return fn(Path<TileCfg<128, 256, 32, 6>, TileCfg<128, 256, 32, 6>, true, false>{});
+  // Prefill batch: 256 x 256 tiles (GEMM1: 128 gate + 128 up weight rows).  Very short
+  // contractions (H or F of 64) get the shallowest ring.
+  if (d.hidden >= 128 && d.ffn >= 128)
+    return fn(Path<TileCfg<256, 256, 32, 4>, TileCfg<256, 256, 32, 4>, false, false>{});
+  return fn(Path<TileCfg<256, 256, 32, 3>, TileCfg<256, 256, 32, 3>, false, false>{});
+}
+
 }  // namespace
 
 prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
                                int32_t* tiles, float* part, float* slice_part, hipStream_t st,
-                               void* const* stage_events, int* deferred_splits,
+                               void* const* stage_events, const int32_t** deferred_splits,
                                bool schedules_built) {
-  if (deferred_splits != nullptr) *deferred_splits = 0;
+  if (deferred_splits != nullptr) *deferred_splits = nullptr;
   if (T == 0) return PRISM_OK;
   const int A = T * d.top_k;
   const int rows = A + d.n_shared * T;
@@ -292,52 +379,12 @@ prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
   if ((size_t)T * d.hidden * 2 >= kMaxOperandBytes || (size_t)rows * d.ffn * 2 >= kMaxOperandBytes ||
       (size_t)d.ffn * d.hidden * 2 >= kMaxOperandBytes)
     return PRISM_ERR_UNSUPPORTED;
-  if (T <= kDecodeMaxTokens) {
-    // Decode batch: every expert has at most 64 rows, the layer is bound by streaming
-    // the weights once.  Small tiles make ~1000 work items; the down projection also
-    // splits its contraction (the slices are summed by a last kernel or by the combine).
-    // No weight tile is shared between workgroups here, so every item starts its
-    // contraction at a different k-tile: at any moment the workgroups then read
-    // different column ranges of the weight rows, whose power-of-two pitch would
-    // otherwise send them all to the same few memory channels.
-    // (ffn_schedule_shapes() below states the tile shapes of all variants)
-    // Tiled weights: 32-wide k-tiles, so that one load instruction takes one whole 1 KiB
-    // tile (with 64-wide k-tiles it would take halves of two), and twice the stages.
-    // An expert has one row tile here, so every weight element is read by exactly one
-    // workgroup, once: the weight loads are marked non-temporal (see STREAM_B).
-    if (d.weight_layout == PRISM_WEIGHTS_TILED && d.hidden >= 256 && d.ffn >= 1024)
-      return run_bf16_ffn<TileCfg<64, 128, 32, 8>, TileCfg<64, 128, 32, 8>, true, true>(
-          d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
-    if (d.hidden >= 192 && d.ffn >= 192)
-      return run_bf16_ffn<TileCfg<64, 128, 64, 4>, TileCfg<64, 128, 64, 4>, true, true>(
-          d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
-    return run_bf16_ffn<TileCfg<64, 128, 32, 3>, TileCfg<64, 128, 32, 3>, true, true>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
-  }
-  // Batches of a few hundred tokens of a wide layer are still bound by streaming the weights
-  // once, but an expert now has up to a few hundred rows.  Tiles twice as wide in weight rows
-  // (256) as in activation rows (128) bring twice the HBM bytes per k-tile for the same waits
-  // and barriers, and the padding rows of a half-empty 256-row tile would cost their loads and
-  // MFMAs like real ones.  (256 x 128 tiles: 0.50 ms for 256 tokens of the 4096 x 14336 layer
-  // with 5 of 8 experts hosted; 128 x 256: 0.43 ms; the 256 x 256 prefill tiles: 0.62 ms,
-  // their down projection has too few items to fill the machine.)  The down projection splits
-  // its contraction as for decode batches.
-  // Up to 128 tokens an expert still has a single row tile (a token picks an expert at most once),
-  // so the weights are read once and stream (0.402 -> 0.389 ms at 128 tokens of the 4096 x 14336
-  // layer); beyond, row tiles share weight tiles through the L2 and the hint costs 8-13 %.
-  if (stream_tiles_apply(d, T) && T <= 128)
-    return run_bf16_ffn<TileCfg<128, 256, 32, 6>, TileCfg<128, 256, 32, 6>, true, true>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
-  if (stream_tiles_apply(d, T))
-    return run_bf16_ffn<TileCfg<128, 256, 32, 6>, TileCfg<128, 256, 32, 6>, true>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
-  // Prefill batch: 256 x 256 tiles (GEMM1: 128 gate + 128 up weight rows).  Very short
-  // contractions (H or F of 64) get the shallowest ring.
-  if (d.hidden >= 128 && d.ffn >= 128)
-    return run_bf16_ffn<TileCfg<256, 256, 32, 4>, TileCfg<256, 256, 32, 4>, false>(
-        d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
-  return run_bf16_ffn<TileCfg<256, 256, 32, 3>, TileCfg<256, 256, 32, 3>, false>(
-      d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits, schedules_built);
+  return select_path(d, T, [&](auto path) {
+    using P = decltype(path);
+    return run_bf16_ffn<typename P::C1, typename P::C2, P::kSplitDown, P::kStreamB>(
+        d, x, w, local_src, local_offsets, T, y, h, tiles, part, slice_part, st, stage_events, deferred_splits,
+        schedules_built);
+  });
 }
 
 // Batches between the decode and the prefill sizes of layers wide enough for the 6-stage ring,
@@ -353,17 +400,11 @@ static bool stream_tiles_apply(const prism_layer_desc& d, int T) {
   return row_tiles * ceil_div(d.hidden, 256) <= 128;
 }
 
-bool ffn_schedule_shapes(const prism_layer_desc& d, int T, int* bm1, int* nt1, int* bm2, int* nt2,
-                         int* slice_kt2) {
-  const bool stream = stream_tiles_apply(d, T);
-  const bool decode = T <= kDecodeMaxTokens;
-  // (row tile, weight rows per tile); all ring depths of a path share the tile
-  const int bm = stream ? 128 : decode ? 64 : 256, bn = stream ? 256 : decode ? 128 : 256;
-  *bm1 = bm; *nt1 = ceil_div(d.ffn, bn / 2);
-  *bm2 = bm; *nt2 = ceil_div(d.hidden, bn);
-  // prefill: the down projection's last round may be cut along its contraction (32-wide k-tiles)
-  *slice_kt2 = !decode && !stream && down_slicing_applies(d, T) ? d.ffn / 32 : 0;
-  return decode || stream;
+FfnShapes ffn_schedule_shapes(const prism_layer_desc& d, int T) {
+  return select_path(d, T, [&](auto path) {
+    using P = decltype(path);
+    return shapes_of<typename P::C1, typename P::C2, P::kSplitDown>(d, T);
+  });
 }
 
 }  // namespace prism

@@ -107,8 +107,9 @@ template <int BK> __device__ __forceinline__ int swizzle_key(int row) {
 // BM x BN output tile per workgroup; BN counts weight rows in the tile (for
 // GATED: BN/2 gate rows and BN/2 up rows).  Wavefronts form a WGM x WGN grid.
 // BK contraction elements per LDS stage (32 or 64), STAGES stages in flight.
-// SPLITK: blockIdx.y selects a slice of the contraction; the tile is written as
-// fp32 partial sums to p.Cpart[slice][row][col] (plain GEMM only).
+// SPLITK: n workgroups share every item, each over its own slice of the contraction, n being
+// what the schedule builder chose (schedule.h, "Splits"); the tile is written as fp32 partial
+// sums to p.Cpart[slice][row][col] (plain GEMM only).
 // ROTATE: every item walks its k-tiles cyclically from an item-dependent start, so
 // concurrent workgroups read different column ranges of their weight rows (for
 // schedules in which workgroups share no weight tiles, i.e. one row tile per group).
@@ -152,14 +153,24 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
 
   // ---- this workgroup's items: slot, slot + slots, ... of its XCD's list -----------
   const int xcd = blockIdx.x % kXcds;
-  const int slot = blockIdx.x / kXcds;
+  int slot = blockIdx.x / kXcds;
   const const_int_ptr sched_c = (const_int_ptr)p.sched;
   const int count = sched_c[(SLICES ? 20 : 4) + xcd];
+  int launched = gridDim.x / kXcds;
+  // SPLITK: the schedule says how many workgroups share an item; neighbouring workgroups of an
+  // XCD take the splits of one item slot, and those left over when the count does not divide the
+  // launch end here.
+  const int n_splits = SPLITK ? max(sched_c[2], 1) : 1;
+  const int split = SPLITK ? slot % n_splits : 0;
+  if (SPLITK) {
+    slot /= n_splits;
+    launched /= n_splits;
+    if (slot >= launched) return;
+  }
   if (slot >= count) return;
   // The list takes ceil(count / launched slots) rounds; the fewest workgroups that still
   // finish in that many rounds share it evenly (a workgroup that would sit out the last
   // round only takes memory bandwidth from the others in the rounds before).
-  const int launched = gridDim.x / kXcds;
   const int rounds = (count + launched - 1) / launched;
   const int slots = (count + rounds - 1) / rounds;
   if (slot >= slots) return;
@@ -176,8 +187,8 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
 
   // this workgroup's slice of the contraction, in k-tiles
   const int KT_all = p.K / BK;
-  const int kt_first = SPLITK ? (int)((long long)KT_all * blockIdx.y / gridDim.y) : 0;
-  const int kt_last = SPLITK ? (int)((long long)KT_all * (blockIdx.y + 1) / gridDim.y) : KT_all;
+  const int kt_first = SPLITK ? (int)((long long)KT_all * split / n_splits) : 0;
+  const int kt_last = SPLITK ? (int)((long long)KT_all * (split + 1) / n_splits) : KT_all;
   const int KT = kt_last - kt_first;
   if (KT <= 0) return;
 
@@ -549,7 +560,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
               if (SPLITK) {
                 const f32x4 o = {acc[i][j][vg * 4], acc[i][j][vg * 4 + 1], acc[i][j][vg * 4 + 2],
                                  acc[i][j][vg * 4 + 3]};
-                *reinterpret_cast<f32x4*>(p.Cpart + ((size_t)blockIdx.y * p.c_rows + crow) * p.N + n) = o;
+                *reinterpret_cast<f32x4*>(p.Cpart + ((size_t)split * p.c_rows + crow) * p.N + n) = o;
               } else {
                 bf16x4 o;
 #pragma unroll
@@ -615,42 +626,47 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
-// Launches the schedule builder for the two GEMMs of the FFN: row tiles bm1 / bm2,
-// nt1 / nt2 column tiles; interleave as in SchedParams.
+// Launches the schedule builder for the two GEMMs of the FFN of a batch of T tokens.
 static inline prism_status launch_build_schedules(const prism_layer_desc& d,
-                                                  const int32_t* local_offsets, int T, int bm1,
-                                                  int nt1, int32_t* sched1, int bm2, int nt2,
-                                                  int32_t* sched2, bool interleave, int slice_kt2,
-                                                  hipStream_t st) {
-  const SchedParams p0{bm1, nt1, sched_capacity(d, T, bm1, nt1), sched1, interleave ? 1 : 0, 0};
-  const SchedParams p1{bm2, nt2, sched_capacity(d, T, bm2, nt2), sched2, interleave ? 1 : 0, slice_kt2};
+                                                  const int32_t* local_offsets, int T,
+                                                  int32_t* tiles, hipStream_t st) {
+  SchedParams p0, p1;
+  ffn_sched_params(d, T, tiles, &p0, &p1);
   hipLaunchKernelGGL(build_schedule_kernel, dim3(2), dim3(512), 0, st, local_offsets, d.n_experts,
                      d.n_shared, T, T * d.top_k, p0, p1);
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;
 }
 
+// LDS of one workgroup of a tile shape, and how many of them a CU holds.
+template <int BM, int BN, int WGN, int BK, int STAGES, bool GATED, bool SPLITK>
+constexpr int gemm_lds_bytes() {
+  return STAGES * (BM + BN) * BK * 2 + (GATED ? 4096 : 0) +           // ring + source-row slots
+         (staged_store<BN / WGN, GATED, SPLITK>() ? 4 * kStripBytes : 0);   // + strips
+}
+constexpr int kCusPerXcd = 32;
+template <int BM, int BN, int WGN, int BK, int STAGES, bool GATED, bool SPLITK>
+constexpr int gemm_wgs_per_xcd() {
+  return kCusPerXcd * ((160 * 1024) / gemm_lds_bytes<BM, BN, WGN, BK, STAGES, GATED, SPLITK>());
+}
+
 // capacity: items per XCD list (sched_capacity).  The grid holds as many workgroups
 // as fit on the machine at once (each then walks several items), or one per item.
 template <int BM, int BN, int WGM, int WGN, int BK, int STAGES, bool GATED, bool SPLITK = false,
           bool ROTATE = false, bool STREAM_B = false, bool SLICES = false>
-prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int n_splits = 1,
-                         int max_slots = 0) {
-  constexpr int smem = STAGES * (BM + BN) * BK * 2 + (GATED ? 4096 : 0) +   // ring + source-row slots
-                       (staged_store<BN / WGN, GATED, SPLITK>() ? 4 * kStripBytes : 0);   // + strips
+prism_status launch_gemm(const GemmArgs& args, int capacity, hipStream_t st, int max_slots = 0) {
+  constexpr int smem = gemm_lds_bytes<BM, BN, WGN, BK, STAGES, GATED, SPLITK>();
   static_assert(smem <= 160 * 1024, "LDS per workgroup");
-  constexpr int kCusPerXcd = 32;
-  constexpr int kResident = (160 * 1024) / smem;     // workgroups per CU that fit in LDS
   auto kernel = grouped_gemm_kernel<BM, BN, WGM, WGN, BK, STAGES, GATED, SPLITK, ROTATE, STREAM_B, SLICES>;
   static LdsLimitOnce lds_limit;   // one per instantiation
   if (!raise_lds_limit(lds_limit, (const void*)kernel, smem)) return PRISM_ERR_LAUNCH;
   if (capacity <= 0) return PRISM_OK;
-  const int splits = SPLITK ? n_splits : 1;
-  int slots = kCusPerXcd * kResident / splits;       // persistent workgroups per XCD
-  if (slots < 1) slots = 1;
+  // persistent workgroups per XCD: as many as are resident at once (SPLITK: the schedule says
+  // how they pair up, so the launch is never cut down to the list length)
+  int slots = gemm_wgs_per_xcd<BM, BN, WGN, BK, STAGES, GATED, SPLITK>();
   if (max_slots > 0) slots = max_slots;
-  if (slots > capacity) slots = capacity;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)(slots * kXcds), splits), dim3(kGemmThreads), smem, st, args);
+  if (!SPLITK && slots > capacity) slots = capacity;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)(slots * kXcds)), dim3(kGemmThreads), smem, st, args);
   PRISM_CHECK_LAUNCH();
   return PRISM_OK;
 }

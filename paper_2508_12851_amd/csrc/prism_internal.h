@@ -31,8 +31,9 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // ---------------------------------------------------------------------------
 constexpr int kDispatchChunk = 2048;   // assignments per dispatch block
 constexpr int kDecodeMaxTokens = 64;    // batches up to this size take the weight-streaming path
-constexpr int kDecodeSplits = 4;        // contraction slices of its down projection (4 beat 8 and 2 when timed)
+constexpr int kDecodeSplits = 8;        // most contraction slices of its down projection (the schedule builder picks how many)
 constexpr int kStreamMaxTokens = 512;   // wide bf16 layers: batches up to this size also split the down projection (expert_ffn.hip)
+constexpr int kMidMaxTokens = 128;      // ... and up to this size an expert still has one row tile of 128 (expert_ffn.hip)
 constexpr int kMinTileM = 64;           // smallest row tile of the grouped GEMM (bounds table sizes)
 constexpr int kRouteTokTile = 16;       // tokens per router tile
 constexpr int kRouteMaxHSplit = 16;     // hidden-dimension slices of the decode router
@@ -179,14 +180,15 @@ prism_status launch_dispatch(const prism_layer_desc& d, const int32_t* topk_idx,
 
 // schedules_built: the two schedules in tiles already exist (decode front end).
 // slice_part: scratch for a cut last round of the down projection (slice_part_bytes).
-// deferred_splits NULL: y holds the finished expert outputs.  Otherwise the decode path leaves
-// its down projection as *deferred_splits (> 0) fp32 contraction slices in part, y unwritten,
-// for launch_combine to sum; *deferred_splits == 0 means y is finished.
+// deferred_splits NULL: y holds the finished expert outputs.  Otherwise the paths that split the
+// down projection's contraction leave it as fp32 slices in part, y unwritten, for launch_combine
+// to sum, and *deferred_splits points at their number in device memory (the schedule builder
+// chose it); *deferred_splits == NULL means y is finished.
 prism_status launch_expert_ffn(const prism_layer_desc& d, const void* x,
                                const prism_expert_weights& w, const int32_t* local_src,
                                const int32_t* local_offsets, int T, void* y, void* h,
                                int32_t* tiles, float* part, float* slice_part, hipStream_t st,
-                               void* const* stage_events, int* deferred_splits,
+                               void* const* stage_events, const int32_t** deferred_splits,
                                bool schedules_built = false);
 
 // True when launch_decode_front_end serves this layer shape and batch.
@@ -204,12 +206,22 @@ prism_status launch_decode_front_end(const prism_layer_desc& d, const void* x, c
                                      int64_t* remote_bytes, int32_t* inv, double* route_part,
                                      int32_t* tiles, hipStream_t st, void* const* stage_events);
 
-// Tile shapes of the two grouped GEMMs of launch_expert_ffn for a bf16 batch of T tokens (row
-// tile, column tiles), which whoever builds their schedules needs, and the k-tiles of the down
-// projection's contraction if the schedule may cut its last round along it (else 0); returns
-// whether the schedules deal their items to the XCDs one by one (decode batches).
-bool ffn_schedule_shapes(const prism_layer_desc& d, int T, int* bm1, int* nt1, int* bm2, int* nt2,
-                         int* slice_kt2);
+// What whoever builds the schedules of launch_expert_ffn's two grouped GEMMs for a bf16 batch of
+// T tokens needs to know about them.
+struct FfnShapes {
+  int bm1, nt1, bm2, nt2;   // row tile and number of column tiles of the gate/up and of the down GEMM
+  bool interleave;          // the items are dealt to the XCDs one by one (batches that stream the weights)
+  int slice_kt2;            // k-tiles of the down projection's contraction if its last round may be cut
+                            // along it; else 0
+  // Down projection whose items are split along the contraction by a count the schedule builder
+  // chooses (schedule.h, "Splits"); split_kt2 == 0: not split.
+  int split_kt2;            // k-tiles of the contraction
+  int split_min_kt2;        // fewest k-tiles of a split
+  int split_wgs2;           // workgroups per XCD of the launch
+  float split_round_kt2;    // fixed cost of a round of items, in k-tiles of one workgroup
+  float split_row_kt2;      // cost of one more fp32 copy of a row, in k-tiles of one workgroup
+};
+FfnShapes ffn_schedule_shapes(const prism_layer_desc& d, int T);
 
 // Records stage_events[2 * stage + end] on st when tracing is on and the pair is set.
 static inline void trace(void* const* ev, int stage, int end, hipStream_t st) {
@@ -225,11 +237,13 @@ prism_status launch_build_inverse(const prism_layer_desc& d, const int32_t* loca
                                   hipStream_t st);
 
 // add_to_out: the gate-weighted rows are added to what out holds (no shared rows, no slices).
-// n_splits > 0: expert outputs are taken from the fp32 slices in part (bf16 layers only),
-// each element summed over the slices and rounded to bf16 as the finished y would hold it.
+// n_splits (device memory) not NULL: expert outputs are taken from *n_splits fp32 slices in part
+// (bf16 layers only), each element summed over the slices in slice order and rounded to bf16 as
+// the finished y would hold it.
 prism_status launch_combine(const prism_layer_desc& d, const void* y, const int32_t* inv,
                             const float* topk_gate, int T, void* out, hipStream_t st,
-                            const float* part = nullptr, int n_splits = 0, bool add_to_out = false);
+                            const float* part = nullptr, const int32_t* n_splits = nullptr,
+                            bool add_to_out = false);
 
 // Row-major bf16 [rows, cols] -> 16 x 32 tiles (rows a multiple of 16, cols of 32).
 prism_status launch_pack_weights(const void* src, int rows, int cols, void* dst, hipStream_t st);

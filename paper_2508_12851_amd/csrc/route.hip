@@ -678,11 +678,8 @@ prism_status launch_decode_front_end(const prism_layer_desc& d, const void* x, c
   const int n_hsplit = ceil_div(d.hidden, route_h_span(d.hidden));
   const dispatch_dev::SplitOut o{local_offsets, remote_offsets, n_local_remote, remote_bytes, counts,
                                  (unsigned long long*)counts_accum, d.hidden * elem_size(d.dtype)};
-  int bm1, nt1, bm2, nt2, slice_kt2;
-  ffn_schedule_shapes(d, T, &bm1, &nt1, &bm2, &nt2, &slice_kt2);   // decode batches: nothing is cut
-  const gg::SchedParams p0{bm1, nt1, gg::sched_capacity(d, T, bm1, nt1), tiles, 1, 0};
-  const gg::SchedParams p1{bm2, nt2, gg::sched_capacity(d, T, bm2, nt2),
-                           tiles + tile_table_ints(d, T), 1, 0};
+  gg::SchedParams p0, p1;
+  gg::ffn_sched_params(d, T, tiles, &p0, &p1);
   trace(stage_events, PRISM_STAGE_DISPATCH, 0, st);
 #define PRISM_FRONT_CASE(NT)                                                                     \
   hipLaunchKernelGGL((decode_front_end_kernel<NT>), dim3(1), dim3(kFrontThreads), 0, st,        \

@@ -18,7 +18,8 @@ constexpr int kSliceSlots = 32;      // workgroups per XCD that sliced lists are
 constexpr int kReduceInts = 8;       // ints per entry of the list of sliced items
 
 // Schedule memory (int32):
-//   [0] n_mtiles  [1] capacity of one XCD list (entries)  [4 + x] items in the list of XCD x
+//   [0] n_mtiles  [1] capacity of one XCD list (entries)  [2] contraction splits (see "Splits")
+//   [4 + x] items in the list of XCD x
 //   [20 + x] slice entries of XCD x (they occupy the last kSliceSlots places of its list)
 //   then, from int kSchedHeader on, 8 lists of `capacity` entries of 8 ints:
 //     [0] group id g (g < E: routed expert g; else shared expert g - E)
@@ -38,6 +39,18 @@ constexpr int kReduceInts = 8;       // ints per entry of the list of sliced ite
 // the last round then takes 1 / s of an item.  The slice entries are run by a launch of their
 // own (one entry per workgroup), each leaving its accumulators as an fp32 partial tile; a
 // small kernel adds the slices of a tile in slice order afterwards.
+//
+// Splits.  The down projection of a batch that is bound by streaming the weights has few
+// items (a decode batch of the 4096 x 14336 layer: 32 column tiles per expert that received a
+// token), so every item is run by `splits` workgroups, each over its own range of k-tiles,
+// leaving fp32 partial sums for a later kernel to add.  How many is decided here, where the
+// number of items is known: s workgroups per item leave floor(w / s) item slots among the w
+// workgroups of an XCD, the list takes ceil(items / slots) rounds of ceil(k-tiles / s) k-tiles
+// each plus a fixed cost per round, and every split writes (and the summing kernel reads) one
+// more fp32 copy of all rows; the s with the lowest sum is taken.  (A model in which the
+// workgroups of a round share the memory bandwidth, so that a thin last round costs less than a
+// full one, was fitted to the same measurements and chose worse: it leaves the 20 items per XCD
+// of five hosted experts whole, 109 us against 96 us with three splits.)
 //
 // Work order.  The (row tile, column tile) grid of every group is cut into rectangles of
 // about kRectRows x kRectCols tiles (a group's row tiles and the column tiles are split
@@ -62,6 +75,13 @@ struct SchedParams {
                      // parts of the weight matrices at any time)
   int slice_kt;      // k-tiles of the contraction if the items of a partly filled last round may be
                      // cut along it (the launch then has kSliceSlots workgroups per XCD); else 0
+  // Contraction splits of every item ("Splits" above); split_kt == 0: the items are not split.
+  int split_kt;      // k-tiles of the contraction
+  int split_max;     // most splits allowed (fp32 copies the partial-sum buffer holds)
+  int split_min_kt;  // fewest k-tiles a split may have (the depth of the kernel's ring)
+  int split_wgs;     // workgroups per XCD of the launch
+  float split_round_kt;   // fixed cost of a round, in k-tiles of one workgroup
+  float split_row_kt;     // cost of one more fp32 copy of one row, in k-tiles of one workgroup
 };
 
 // Where the list of sliced items starts (ints from the start of the schedule).
@@ -144,6 +164,25 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
     if (part == 0) {
       ps.sched[0] = run;
       ps.sched[1] = ps.capacity;
+      int splits = 1;
+      if (ps.split_kt > 0) {
+        int rows_total = 0;
+        for (int g = 0; g < G; ++g) rows_total += s_rows[g];
+        const int longest = (int)((total + kXcds - 1) / kXcds);   // items of the longest XCD list
+        float best = 0.f;
+        for (int sp = 1; sp <= ps.split_max; ++sp) {
+          const int slots = ps.split_wgs / sp;
+          if (slots < 1 || ps.split_kt / sp < ps.split_min_kt) break;
+          const int rounds = (longest + slots - 1) / slots;
+          const float cost = (float)rounds * ((float)((ps.split_kt + sp - 1) / sp) + ps.split_round_kt) +
+                             (float)sp * (float)rows_total * ps.split_row_kt;
+          if (sp == 1 || cost < best) {
+            best = cost;
+            splits = sp;
+          }
+        }
+      }
+      ps.sched[2] = splits;
     }
     for (unsigned x = 0; part == 0 && x < (unsigned)kXcds; ++x) {
       unsigned count;
@@ -233,6 +272,18 @@ static inline int max_row_tiles(const prism_layer_desc& d, int T, int BM) {
 // tiles, plus the slices a cut last round adds (at most one entry per workgroup).
 static inline int sched_capacity(const prism_layer_desc& d, int T, int BM, int n_ntiles) {
   return max_row_tiles(d, T, BM) * ceil_div(n_ntiles, kXcds) + kSliceSlots;
+}
+
+// Parameters of the two schedules of launch_expert_ffn for a bf16 batch of T tokens, which live
+// side by side in `tiles` (2 x tile_table_ints): what every kernel that builds them is given.
+static inline void ffn_sched_params(const prism_layer_desc& d, int T, int32_t* tiles, SchedParams* p0,
+                                    SchedParams* p1) {
+  const FfnShapes f = ffn_schedule_shapes(d, T);
+  *p0 = SchedParams{f.bm1, f.nt1, sched_capacity(d, T, f.bm1, f.nt1), tiles, f.interleave ? 1 : 0,
+                    0, 0, 0, 0, 0, 0.f, 0.f};
+  *p1 = SchedParams{f.bm2, f.nt2, sched_capacity(d, T, f.bm2, f.nt2), tiles + tile_table_ints(d, T),
+                    f.interleave ? 1 : 0, f.slice_kt2, f.split_kt2, kDecodeSplits, f.split_min_kt2,
+                    f.split_wgs2, f.split_round_kt2, f.split_row_kt2};
 }
 
 }  // namespace gg

@@ -87,11 +87,21 @@ def test_cfg3_mixtral_decode_full_size():
     _full_parity(cfg, inp, "cfg3")
 
 
-@pytest.mark.parametrize("T", [200, 512, 1024, 1536, 2048])
+@pytest.mark.parametrize("n_local", [1, 3, 8])
+def test_mixtral_decode_with_other_numbers_of_hosted_experts(n_local):
+    """The decode batch with 1, 3 and all 8 experts hosted: the schedule builder splits the down
+    projection's contraction into a number of slices that depends on how many experts received
+    tokens (from one workgroup per item to eight)."""
+    cfg = make_config("cfg3_mixtral_decode", n_local=n_local)
+    inp = make_inputs(cfg, weights="local", threads=16)
+    _full_parity(cfg, inp, f"Mixtral decode, {n_local} hosted", layouts=("tiled",))
+
+
+@pytest.mark.parametrize("T", [96, 128, 200, 512, 1024, 1536, 2048])
 def test_mixtral_shape_other_batch_sizes_full_size(T):
-    """The full Mixtral layer shape between the decode and the benchmark batch: 128 x 256 tiles
-    with the split down projection up to 512 tokens, prefill tiles whose last round of work
-    items is only partly filled above."""
+    """The full Mixtral layer shape between the decode and the benchmark batch: 128 x 128 tiles
+    up to 128 tokens, 128 x 256 tiles up to 352, both with the split down projection; prefill
+    tiles whose last round of work items is only partly filled above."""
     cfg = make_config("cfg2_mixtral_prefill", T=T)
     inp = make_inputs(cfg, weights="local", threads=16)
     _full_parity(cfg, inp, f"Mixtral shape, {T} tokens", layouts=("tiled",))
