@@ -111,13 +111,15 @@ __device__ __forceinline__ HistSums sum_block_hists(const int32_t* __restrict__ 
 // the bucket starts from it and, if it is block 0, writes the outputs in o.
 // Otherwise the whole batch is one chunk: the workgroup histograms it itself (block_hist
 // is not read) and writes the outputs.
-// idx may have been written earlier in the same kernel by this workgroup (with a
-// __syncthreads() in between), hence no __restrict__ on it.
+// idx may have been written earlier in the same kernel by this workgroup (to memory with a
+// __syncthreads() in between, or to LDS with a barrier), hence no __restrict__ on it.
+// s_local_off (LDS, [E + 1], only without FROM_HIST): also receives the local offsets.
 template <bool FROM_HIST>
 __device__ __forceinline__ void dispatch_place_block(
     const int32_t* idx, int A, int E, const uint8_t* __restrict__ mask,
     const int32_t* __restrict__ block_hist, int n_blocks, int sub, int block, const SplitOut& o,
-    int32_t* __restrict__ local_src, int32_t* __restrict__ remote_src, int32_t* __restrict__ inv) {
+    int32_t* __restrict__ local_src, int32_t* __restrict__ remote_src, int32_t* __restrict__ inv,
+    int* s_local_off = nullptr) {
   static_assert(PRISM_MAX_EXPERTS <= kThreads, "one thread per expert");
   // Only LDS data crosses between threads in here, so the barriers do not wait for
   // the global stores.
@@ -165,7 +167,7 @@ __device__ __forceinline__ void dispatch_place_block(
         s_total[e] = t;
       }
       lds_barrier();
-      if (threadIdx.x < kWave) split_offsets(s_total, s_mask, E, o, s_run);
+      if (threadIdx.x < kWave) split_offsets(s_total, s_mask, E, o, s_run, true, s_local_off);
       lds_barrier();
     }
     if (threadIdx.x < E) {

@@ -113,6 +113,8 @@ template <int BK> __device__ __forceinline__ int swizzle_key(int row) {
 // ROTATE: every item walks its k-tiles cyclically from an item-dependent start, so
 // concurrent workgroups read different column ranges of their weight rows (for
 // schedules in which workgroups share no weight tiles, i.e. one row tile per group).
+// These are the schedules that deal their items to the XCDs one by one; the kernel works out
+// its items from the schedule's table of row tiles (schedule.h) instead of reading lists.
 // STREAM_B: the weight loads carry the non-temporal hint.  For batches in which every weight
 // tile is read by one workgroup only (one row tile per expert) the weights cross the memory
 // system once, and reads marked that way stream from HBM about 15 % faster than plain ones
@@ -219,8 +221,16 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
     uint32_t a_voff[A_CH];
     uint32_t b_voff[B_CH];
   };
+  // ROTATE schedules hold one line per row tile instead of item lists (schedule.h)
+  const int n_ntiles = (p.N + (GATED ? BN / 2 : BN) - 1) / (GATED ? BN / 2 : BN);
   auto fetch_item = [&](int idx) {   // idx is clamped: the result is only used when idx < count
     const int i = min(idx, count - 1);
+    if (ROTATE) {
+      const unsigned seq = (unsigned)i * kXcds + (unsigned)xcd;
+      const unsigned tile = seq / (unsigned)n_ntiles;
+      const int4 h0 = ((const_int4_ptr)(p.sched + kSchedHeader))[tile];
+      return Item{h0.x, h0.y, h0.z, h0.w, (int)(seq - tile * (unsigned)n_ntiles), 0, KT, -1};
+    }
     const int4 h0 = items[2 * i];
     const int4 h1 = items[2 * i + 1];
     if (SLICES) return Item{h0.x, h0.y, h0.z, h0.w, h1.x, h1.y, h1.z, h1.w};

@@ -67,7 +67,8 @@ template <int NT>
 __device__ __forceinline__ void finish_group(const double (&s)[NT], const float (&b)[NT],
                                              bool has_bias, int t, int T, int E, int k, int gate_mode,
                                              float* __restrict__ logits, int32_t* topk_idx,
-                                             float* __restrict__ topk_gate, int* s_counts) {
+                                             float* __restrict__ topk_gate, int* s_counts,
+                                             int32_t* s_idx = nullptr) {
   const int r = threadIdx.x & 15;
   // ---- one rounding to fp32, then the fp32 bias add --------------------------
   float lg[NT];
@@ -123,6 +124,7 @@ __device__ __forceinline__ void finish_group(const double (&s)[NT], const float 
   for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
   if (r < k && t < T) {
     topk_idx[(size_t)t * k + r] = myidx;
+    if (s_idx != nullptr) s_idx[t * k + r] = myidx;   // a copy in LDS for what follows in the same kernel
     topk_gate[(size_t)t * k + r] = (float)(w / sum);
     if (s_counts != nullptr) atomicAdd(&s_counts[myidx], 1);
   }
@@ -137,7 +139,8 @@ __device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0, in
                                             const float* __restrict__ bias, int T, int E, int k,
                                             int bias_group_tokens, int gate_mode,
                                             float* __restrict__ logits, int32_t* topk_idx,
-                                            float* __restrict__ topk_gate, int* s_counts) {
+                                            float* __restrict__ topk_gate, int* s_counts,
+                                            int32_t* s_idx = nullptr) {
   const int q = (threadIdx.x & 63) >> 4;
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
@@ -149,7 +152,7 @@ __device__ __forceinline__ void finish_tile(const f64x4 (&acc)[NT], int tok0, in
     for (int n = 0; n < NT; ++n) s[n] = acc[n][v];
     load_bias_group<NT>(bias, t, T, E, bias_group_tokens, b);
     finish_group<NT>(s, b, bias != nullptr, t, T, E, k, gate_mode, logits, topk_idx, topk_gate,
-                     s_counts);
+                     s_counts, s_idx);
   }
 }
 
@@ -494,14 +497,15 @@ __global__ void fill_i32_kernel(int32_t* p, int n, int32_t v) {
 }
 
 // Decode front end, second launch (one workgroup): sums the hidden-dimension slices of
-// every token tile in slice order (in place, into slice 0), finishes the routing (one wavefront per tile of 16
-// tokens, at most 4 tiles), then splits the T*k assignments by placement and builds the
-// schedules of the two grouped GEMMs.  The steps hand their results to each other
-// through memory, separated by workgroup barriers.
+// every token tile in slice order and finishes the routing (each wavefront four tokens of
+// every tile), then splits the T*k assignments by placement and builds the schedules of the
+// two grouped GEMMs.  The kernel is a chain of short dependent steps on the critical path of
+// the layer, so the steps hand their results to each other in LDS (expert indices, local
+// offsets): no step waits for a store to memory or re-reads what the step before wrote there.
 constexpr int kFrontThreads = dispatch_dev::kThreads;
 template <int NT>
 __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
-    double* partial, int n_hsplit, const float* __restrict__ bias, int T, int E,
+    const double* __restrict__ partial, int n_hsplit, const float* __restrict__ bias, int T, int E,
     int k, int S, int bias_group_tokens, int gate_mode, int32_t* topk_idx,
     float* __restrict__ topk_gate,
     const uint8_t* __restrict__ mask, const dispatch_dev::SplitOut o,
@@ -510,45 +514,68 @@ __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int n_tiles = (T + kTokPerBlock - 1) / kTokPerBlock;
-  // Slice sums, all threads: element j of tile t (a 4-double vector of the NT * 64 that
-  // make a tile) is added up over the slices in slice order and left in slice 0's place.
-  for (int item = threadIdx.x; item < n_tiles * NT * 64; item += kFrontThreads) {
-    const int tile = item / (NT * 64), j = item % (NT * 64);
-    double* base = partial + (size_t)tile * n_hsplit * (NT * 256) + j * 4;
-    f64x4 part[kRouteMaxHSplit];
-#pragma unroll
-    for (int y = 0; y < kRouteMaxHSplit; ++y)   // slices past the end re-read the last one (unused)
-      part[y] = *reinterpret_cast<const f64x4*>(base + (size_t)min(y, n_hsplit - 1) * (NT * 256));
-    f64x4 sum = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int y = 0; y < kRouteMaxHSplit; ++y) {
-      const bool on = y < n_hsplit;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) sum[v] += on ? part[y][v] : 0.0;
-    }
-    *reinterpret_cast<f64x4*>(base) = sum;
-  }
-  __syncthreads();   // the sums are visible to the whole workgroup
+  __shared__ int32_t s_idx[kDispatchChunk];                 // topk_idx, for the split
+  __shared__ int s_local_off[PRISM_MAX_EXPERTS + 1];        // local_offsets, for the schedules
   // A tile's routing is four units of four tokens (accumulator register v holds tokens
   // 4v + q); wavefront w takes unit v = w of every tile, so even a 16-token batch keeps all
-  // four wavefronts busy.
+  // four wavefronts busy.  The logits are the sums over the router's slices, in slice order.
   static_assert(kFrontThreads / kWave == 4, "one wavefront per accumulator register index");
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    const int v_mask = 1 << wave;
-    f64x4 acc[NT];
+  constexpr int kMaxTiles = kDecodeMaxTokens / kTokPerBlock;
+  if constexpr (NT <= 4) {
+    // All threads share the slice sums -- element j of tile t is a 4-double vector of the
+    // NT * 64 that make a tile, its 16 slice loads issued together -- and leave them in LDS.
+    __shared__ __align__(32) double s_sum[kMaxTiles * NT * 256];
+    for (int item = threadIdx.x; item < n_tiles * NT * 64; item += kFrontThreads) {
+      const int tile = item / (NT * 64), j = item % (NT * 64);
+      const double* base = partial + (size_t)tile * n_hsplit * (NT * 256) + j * 4;
+      f64x4 part[kRouteMaxHSplit];
 #pragma unroll
-    for (int n = 0; n < NT; ++n)
-      acc[n] = *reinterpret_cast<const f64x4*>(partial + (size_t)tile * n_hsplit * (NT * 256) +
-                                               n * 256 + lane * 4);
-    finish_tile<NT>(acc, tile * kTokPerBlock, v_mask, bias, T, E, k, bias_group_tokens, gate_mode,
-                    nullptr, topk_idx, topk_gate, nullptr);
+      for (int y = 0; y < kRouteMaxHSplit; ++y)   // slices past the end re-read the last one (unused)
+        part[y] = *reinterpret_cast<const f64x4*>(base + (size_t)min(y, n_hsplit - 1) * (NT * 256));
+      f64x4 sum = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int y = 0; y < kRouteMaxHSplit; ++y) {
+        const bool on = y < n_hsplit;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sum[v] += on ? part[y][v] : 0.0;
+      }
+      *reinterpret_cast<f64x4*>(s_sum + (size_t)tile * (NT * 256) + j * 4) = sum;
+    }
+    lds_barrier();
+    for (int tile = 0; tile < n_tiles; ++tile) {
+      f64x4 acc[NT];
+#pragma unroll
+      for (int n = 0; n < NT; ++n)
+        acc[n] = *reinterpret_cast<const f64x4*>(s_sum + (size_t)tile * (NT * 256) + n * 256 + lane * 4);
+      finish_tile<NT>(acc, tile * kTokPerBlock, 1 << wave, bias, T, E, k, bias_group_tokens, gate_mode,
+                      nullptr, topk_idx, topk_gate, nullptr, s_idx);
+    }
+  } else {
+    // Too many expert columns for LDS: every wavefront sums the component it needs itself.
+    for (int tile = 0; tile < n_tiles; ++tile) {
+      const double* base = partial + (size_t)tile * n_hsplit * (NT * 256) + lane * 4 + wave;
+      f64x4 acc[NT];
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+        double part[kRouteMaxHSplit];
+#pragma unroll
+        for (int y = 0; y < kRouteMaxHSplit; ++y)
+          part[y] = base[(size_t)min(y, n_hsplit - 1) * (NT * 256) + n * 256];
+        double sum = 0.0;
+#pragma unroll
+        for (int y = 0; y < kRouteMaxHSplit; ++y) sum += y < n_hsplit ? part[y] : 0.0;
+        acc[n] = f64x4{sum, sum, sum, sum};         // finish_tile reads component `wave` only
+      }
+      finish_tile<NT>(acc, tile * kTokPerBlock, 1 << wave, bias, T, E, k, bias_group_tokens, gate_mode,
+                      nullptr, topk_idx, topk_gate, nullptr, s_idx);
+    }
   }
-  __syncthreads();   // topk_idx is complete and visible to the whole workgroup
-  dispatch_dev::dispatch_place_block<false>(topk_idx, T * k, E, mask, nullptr, 1, 1, 0, o, local_src,
-                                            remote_src, inv);
-  __syncthreads();   // local_offsets (written by the split) is visible to the whole workgroup
+  lds_barrier();   // s_idx is complete (the copy in memory is for the caller)
+  dispatch_dev::dispatch_place_block<false>(s_idx, T * k, E, mask, nullptr, 1, 1, 0, o, local_src,
+                                            remote_src, inv, s_local_off);
+  lds_barrier();   // s_local_off, written by the split
   const gg::SchedParams p[2] = {p0, p1};
-  gg::build_schedules_block<2>(o.local_offsets, E, S, T, T * k, p);
+  gg::build_schedules_block<2>(s_local_off, E, S, T, T * k, p);
 }
 
 // Hidden elements per workgroup of the split router: a multiple of the 256 elements one

@@ -21,7 +21,12 @@ constexpr int kReduceInts = 8;       // ints per entry of the list of sliced ite
 //   [0] n_mtiles  [1] capacity of one XCD list (entries)  [2] contraction splits (see "Splits")
 //   [4 + x] items in the list of XCD x
 //   [20 + x] slice entries of XCD x (they occupy the last kSliceSlots places of its list)
-//   then, from int kSchedHeader on, 8 lists of `capacity` entries of 8 ints:
+//   then, from int kSchedHeader on, for schedules that deal their items to the XCDs one by
+//   one (interleave): one line of 4 ints per row tile, [0]..[3] as below -- item number seq is
+//   row tile seq / (column tiles), column tile seq mod (column tiles), and XCD x runs the items
+//   x, x + 8, ...; the kernel works that out itself, which keeps the builder, a serial step on
+//   the critical path of a decode layer, from writing a thousand entries --
+//   for all other schedules 8 lists of `capacity` entries of 8 ints:
 //     [0] group id g (g < E: routed expert g; else shared expert g - E)
 //     [1] first row of the row tile in h / y row space
 //     [2] rows in the tile (1..BM)
@@ -52,18 +57,16 @@ constexpr int kReduceInts = 8;       // ints per entry of the list of sliced ite
 // full one, was fitted to the same measurements and chose worse: it leaves the 20 items per XCD
 // of five hosted experts whole, 109 us against 96 us with three splits.)
 //
-// Work order.  The (row tile, column tile) grid of every group is cut into rectangles of
-// about kRectRows x kRectCols tiles (a group's row tiles and the column tiles are split
-// into equal parts no larger than that).  All items, rectangle after rectangle (groups in
-// order, row parts, then column parts; inside a rectangle the row tiles run fastest), form
-// one sequence, and XCD x gets the x-th eighth of it.  So the 32 workgroups resident on an
-// XCD work at any time on one or two rectangles -- about 8 activation tiles and 4 weight
-// tiles for 32 items instead of one of each per item -- which is what the XCD's L2 can
-// share among them, and the eight lists have the same length to within one item.
+// Work order.  A group's row tiles are split into equal parts of at most kRectRows.  All
+// items -- groups in order, then row parts, then the column tiles of a row part, the row tiles
+// of a column running fastest -- form one sequence, and XCD x gets the x-th eighth of it.  So
+// the 32 workgroups resident on an XCD work at any time on a rectangle of about 8 row tiles x
+// 4 column tiles -- 8 activation tiles and 4 weight tiles for 32 items instead of one of each
+// per item -- which is what the XCD's L2 can share among them, and the eight lists have the
+// same length to within one item.
 // The number of items (row tiles x column tiles) must stay below 2^31, which the int
 // capacity of a list already implies.
 constexpr int kRectRows = 8;
-constexpr int kRectCols = 4;
 
 struct SchedParams {
   int BM;            // row tile
@@ -72,7 +75,8 @@ struct SchedParams {
   int32_t* sched;
   int interleave;    // 1: deal the sequence to the XCDs item by item instead of in eighths
                      // (schedules whose items share nothing: every XCD then reads from all
-                     // parts of the weight matrices at any time)
+                     // parts of the weight matrices at any time); the schedule then holds a
+                     // table of row tiles instead of item lists
   int slice_kt;      // k-tiles of the contraction if the items of a partly filled last round may be
                      // cut along it (the launch then has kSliceSlots workgroups per XCD); else 0
   // Contraction splits of every item ("Splits" above); split_kt == 0: the items are not split.
@@ -120,7 +124,7 @@ __device__ __forceinline__ Slicing slicing_of(int n, int slice_kt) {
 }
 
 // Builds NS (1 or 2) schedules of the same row groups side by side; called by every
-// thread of a workgroup (any size that is a multiple of 64).  Inside, only LDS data
+// thread of a workgroup (any size that is a multiple of 64, at least NS wavefronts).  Inside, only LDS data
 // crosses between threads, so the barriers do not wait for the global stores.
 // local_offsets (global memory or LDS) may have been written earlier in the same kernel by
 // this workgroup (with a barrier in between), hence no __restrict__ on it.
@@ -150,49 +154,69 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
     s_row0[g] = row0;
   }
   lds_barrier();
-  if (threadIdx.x < NS) {
-    const int s = threadIdx.x;
+  // Wavefront s prepares schedule s: first row tile of every group (a scan over the groups, 64
+  // at a time), the header, and the number of contraction splits -- in parallel over its lanes,
+  // because this is a serial step on the critical path of a decode layer.
+  const int lane = threadIdx.x & 63;
+  if ((int)(threadIdx.x >> 6) < NS) {
+    const int s = threadIdx.x >> 6;
     const SchedParams ps = pick(s);
-    int run = 0;
-    for (int g = 0; g < G; ++g) {
-      s_start[s][g] = run;
-      run += (s_rows[g] + ps.BM - 1) / ps.BM;
+    int run = 0, rows_total = 0;
+    for (int g0 = 0; g0 < G; g0 += 64) {
+      const int g = g0 + lane;
+      const int rows = g < G ? s_rows[g] : 0;
+      const int tiles = (rows + ps.BM - 1) / ps.BM;
+      int incl = tiles, rsum = rows;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int a = __shfl_up(incl, off);
+        if (lane >= off) incl += a;
+      }
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) rsum += __shfl_xor(rsum, off);
+      if (g < G) s_start[s][g] = run + incl - tiles;
+      run += __shfl(incl, 63);
+      rows_total += rsum;
     }
-    s_start[s][G] = run;
+    if (lane == 0) s_start[s][G] = run;
     const unsigned total = (unsigned)run * (unsigned)ps.n_ntiles;
     const unsigned per_xcd = (total + kXcds - 1) / kXcds;
     if (part == 0) {
-      ps.sched[0] = run;
-      ps.sched[1] = ps.capacity;
-      int splits = 1;
-      if (ps.split_kt > 0) {
-        int rows_total = 0;
-        for (int g = 0; g < G; ++g) rows_total += s_rows[g];
-        const int longest = (int)((total + kXcds - 1) / kXcds);   // items of the longest XCD list
-        float best = 0.f;
-        for (int sp = 1; sp <= ps.split_max; ++sp) {
-          const int slots = ps.split_wgs / sp;
-          if (slots < 1 || ps.split_kt / sp < ps.split_min_kt) break;
-          const int rounds = (longest + slots - 1) / slots;
-          const float cost = (float)rounds * ((float)((ps.split_kt + sp - 1) / sp) + ps.split_round_kt) +
-                             (float)sp * (float)rows_total * ps.split_row_kt;
-          if (sp == 1 || cost < best) {
-            best = cost;
-            splits = sp;
-          }
+      if (lane == 0) {
+        ps.sched[0] = run;
+        ps.sched[1] = ps.capacity;
+      }
+      if (lane < kXcds) {
+        const unsigned x = lane;
+        unsigned count;
+        if (ps.interleave)   // items x, x + 8, ...
+          count = total > x ? (total - x + kXcds - 1) / kXcds : 0;
+        else                 // every list holds per_xcd items, the last non-empty one the remainder
+          count = total > x * per_xcd ? min(per_xcd, total - x * per_xcd) : 0;
+        const Slicing sl = slicing_of((int)count, ps.slice_kt);
+        ps.sched[4 + x] = (int)count - sl.items;
+        ps.sched[20 + x] = sl.items * sl.slices;
+      }
+      // lane sp - 1 prices sp splits; the cheapest wins, the lower count on ties
+      const int sp = lane + 1;
+      const int slots = ps.split_wgs / sp;
+      float cost = INFINITY;
+      if (ps.split_kt > 0 && sp <= ps.split_max && slots >= 1 && ps.split_kt / sp >= ps.split_min_kt) {
+        const int rounds = ((int)per_xcd + slots - 1) / slots;   // per_xcd: the longest XCD list
+        cost = (float)rounds * ((float)((ps.split_kt + sp - 1) / sp) + ps.split_round_kt) +
+               (float)sp * (float)rows_total * ps.split_row_kt;
+      }
+      int best = sp;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        const float oc = __shfl_xor(cost, off);
+        const int ob = __shfl_xor(best, off);
+        if (oc < cost || (oc == cost && ob < best)) {
+          cost = oc;
+          best = ob;
         }
       }
-      ps.sched[2] = splits;
-    }
-    for (unsigned x = 0; part == 0 && x < (unsigned)kXcds; ++x) {
-      unsigned count;
-      if (ps.interleave)   // items x, x + 8, ...
-        count = total > x ? (total - x + kXcds - 1) / kXcds : 0;
-      else                 // every list holds per_xcd items, the last non-empty one the remainder
-        count = total > x * per_xcd ? min(per_xcd, total - x * per_xcd) : 0;
-      const Slicing sl = slicing_of((int)count, ps.slice_kt);
-      ps.sched[4 + x] = (int)count - sl.items;
-      ps.sched[20 + x] = sl.items * sl.slices;
+      if (lane == 0) ps.sched[2] = cost < INFINITY ? best : 1;
     }
   }
   lds_barrier();
@@ -211,23 +235,35 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
     };
     const unsigned n_items = (unsigned)n_mtiles * (unsigned)n_ntiles;
     const unsigned per_xcd = (n_items + kXcds - 1) / kXcds;
+    if (interleave) {
+      // no lists: the kernel derives item seq = tile * n_ntiles + column tile from its position
+      // (XCD x takes seq = x, x + 8, ...) and reads the row tile's line of this table
+      int4* table = reinterpret_cast<int4*>(p[s].sched + kSchedHeader);
+      for (int i = part * blockDim.x + threadIdx.x; i < n_mtiles; i += n_parts * blockDim.x) {
+        const int g = group_of_tile(i);
+        const int mi = i - s_start[s][g];
+        table[i] = int4{g, s_row0[g] + mi * BM, min(BM, s_rows[g] - mi * BM), g < E ? -1 : mi * BM};
+      }
+      continue;
+    }
     for (unsigned w = part * blockDim.x + threadIdx.x; w < n_items; w += n_parts * blockDim.x) {
-      const int i = (int)(w % (unsigned)n_mtiles), nt = (int)(w / (unsigned)n_mtiles);
+      const int nt = (int)(w / (unsigned)n_mtiles), i = (int)(w - (unsigned)nt * (unsigned)n_mtiles);
       const int g = group_of_tile(i);
       const int mi = i - s_start[s][g];
       const int m = s_start[s][g + 1] - s_start[s][g];
-      const PartOf rp = part_of(mi, m, kRectRows);          // this item's rectangle: rows ...
-      const PartOf cp = part_of(nt, n_ntiles, kRectCols);   // ... and columns
-      // items before it: earlier groups, earlier row parts of its group, earlier rectangles of
-      // its row part, earlier columns of its rectangle, earlier rows of its column
+      // this item's row part (most groups have a single one: no division then)
+      const PartOf rp = m <= kRectRows ? PartOf{0, m} : part_of(mi, m, kRectRows);
+      // items before it: earlier groups, earlier row parts of its group, earlier columns of its
+      // row part (which is the rectangle order: the rectangles of a row part follow each other
+      // column by column), earlier rows of its column
       const unsigned seq = (unsigned)(s_start[s][g] + rp.first) * (unsigned)n_ntiles +
-                           (unsigned)(rp.len * cp.first + (nt - cp.first) * rp.len + (mi - rp.first));
-      const unsigned x = interleave ? seq % kXcds : seq / per_xcd;
-      const unsigned pos = interleave ? seq / kXcds : seq - x * per_xcd;
+                           (unsigned)(nt * rp.len + (mi - rp.first));
+      const unsigned x = seq / per_xcd;
+      const unsigned pos = seq - x * per_xcd;
       const int4 head = int4{g, s_row0[g] + mi * BM, min(BM, s_rows[g] - mi * BM), g < E ? -1 : mi * BM};
       int4* list = reinterpret_cast<int4*>(p[s].sched + kSchedHeader + (size_t)x * capacity * kItemInts);
-      const unsigned in_list = interleave ? 0u : (n_items > x * per_xcd ? min(per_xcd, n_items - x * per_xcd) : 0u);
-      const Slicing sl = slicing_of((int)in_list, interleave ? 0 : p[s].slice_kt);
+      const unsigned in_list = n_items > x * per_xcd ? min(per_xcd, n_items - x * per_xcd) : 0u;
+      const Slicing sl = slicing_of((int)in_list, p[s].slice_kt);
       const int first_sliced = (int)in_list - sl.items;
       if ((int)pos < first_sliced || sl.slices == 0) {
         list[2 * pos] = head;
@@ -250,7 +286,7 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
       }
     }
     // lines of the list of sliced items that this call does not use are marked empty
-    if (!interleave && p[s].slice_kt > 0)
+    if (p[s].slice_kt > 0)
       for (int r = part * blockDim.x + threadIdx.x; r < kXcds * (kSliceSlots / 2); r += n_parts * blockDim.x) {
         const unsigned x = (unsigned)r / (kSliceSlots / 2);
         const int li = r % (kSliceSlots / 2);
