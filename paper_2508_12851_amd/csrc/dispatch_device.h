@@ -47,12 +47,7 @@ __device__ __forceinline__ void split_offsets(const int* s_total, const uint8_t*
     tot[j] = e < E ? s_total[e] : 0;
     if (e < E && s_mask[e]) loc += tot[j]; else rem += tot[j];
   }
-  int loc_incl = loc, rem_incl = rem;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int a = __shfl_up(loc_incl, off), b = __shfl_up(rem_incl, off);
-    if (lane >= off) { loc_incl += a; rem_incl += b; }
-  }
+  const int loc_incl = wave_inclusive_scan(loc), rem_incl = wave_inclusive_scan(rem);
   int nl = loc_incl - loc, nr = rem_incl - rem;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {

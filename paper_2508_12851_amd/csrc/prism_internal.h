@@ -263,6 +263,44 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// Cross-lane moves inside the vector ALU (data-parallel primitives: no trip through the LDS
+// crossbar, which a __shfl costs).  The single-workgroup kernels on the critical path of a
+// decode layer are chains of short dependent steps, and their reductions and scans are a large
+// part of those chains.
+//   row_xor<OFF>(v): the value of lane (lane ^ OFF), OFF in {1, 2, 4, 8} (lanes of one
+//   16-lane row exchange: quad permutes for 1 and 2, a shift left / right by 4 chosen per
+//   bank of 4 lanes, a rotation by 8).
+//   wave_inclusive_scan(v): sum of v over lanes 0..lane of the wavefront.
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF>
+__device__ __forceinline__ int dpp_move(int old, int src) {
+  return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, BANK_MASK, false);
+}
+template <int OFF> __device__ __forceinline__ int row_xor(int v) {
+  static_assert(OFF == 1 || OFF == 2 || OFF == 4 || OFF == 8, "inside a row of 16 lanes");
+  if constexpr (OFF == 1) return dpp_move<0xB1>(v, v);                 // quad_perm [1,0,3,2]
+  else if constexpr (OFF == 2) return dpp_move<0x4E>(v, v);            // quad_perm [2,3,0,1]
+  else if constexpr (OFF == 4)                                         // banks 0, 2: lane + 4; banks 1, 3: lane - 4
+    return dpp_move<0x114, 0xF, 0xA>(dpp_move<0x104, 0xF, 0x5>(v, v), v);
+  else return dpp_move<0x128>(v, v);                                   // row_ror:8
+}
+template <int OFF> __device__ __forceinline__ float row_xor(float v) {
+  return __int_as_float(row_xor<OFF>(__float_as_int(v)));
+}
+template <int OFF> __device__ __forceinline__ double row_xor(double v) {
+  const long long b = __double_as_longlong(v);
+  const int lo = row_xor<OFF>((int)(unsigned)b), hi = row_xor<OFF>((int)(unsigned)((unsigned long long)b >> 32));
+  return __longlong_as_double((long long)(((unsigned long long)(unsigned)hi << 32) | (unsigned)lo));
+}
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += dpp_move<0x111>(0, v);          // row_shr:1 (lanes without a source add 0)
+  v += dpp_move<0x112>(0, v);          // row_shr:2
+  v += dpp_move<0x114>(0, v);          // row_shr:4
+  v += dpp_move<0x118>(0, v);          // row_shr:8 -> inclusive scan of every row of 16
+  v += dpp_move<0x142, 0xA>(0, v);     // row_bcast:15 -> rows 1 and 3 add the total of rows 0 and 2
+  v += dpp_move<0x143, 0xC>(0, v);     // row_bcast:31 -> rows 2 and 3 add the total of rows 0..1
+  return v;
+}
+
 // Direct global -> LDS loads (buffer_load_dwordx4 ... lds): raw buffer resources whose size
 // makes a lane offset at or above it read zeros (the scalar offset of a load is not part of
 // that check), and the vector-memory counter the loads are awaited with.

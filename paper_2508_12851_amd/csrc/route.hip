@@ -85,7 +85,7 @@ __device__ __forceinline__ void finish_group(const double (&s)[NT], const float 
     lg[n] = val;
   }
 
-  // ---- top-k: k rounds of arg-max over (logit, expert index) with xor-shuffles inside the
+  // ---- top-k: k rounds of arg-max over (logit, expert index) with xor-exchanges inside the
   // group; equal logits resolve to the lower expert index.
   float vals[NT];
 #pragma unroll
@@ -98,12 +98,13 @@ __device__ __forceinline__ void finish_group(const double (&s)[NT], const float 
 #pragma unroll
     for (int n = 1; n < NT; ++n)
       if (vals[n] > best) { best = vals[n]; bidx = n * 16 + r; }
-#pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) {
-      const float ov = __shfl_xor(best, off);
-      const int oi = __shfl_xor(bidx, off);
+    auto meet = [&](float ov, int oi) {
       if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
-    }
+    };
+    meet(row_xor<8>(best), row_xor<8>(bidx));
+    meet(row_xor<4>(best), row_xor<4>(bidx));
+    meet(row_xor<2>(best), row_xor<2>(bidx));
+    meet(row_xor<1>(best), row_xor<1>(bidx));
     // every lane of the group holds the winner; its owner retires it
 #pragma unroll
     for (int n = 0; n < NT; ++n)
@@ -120,8 +121,10 @@ __device__ __forceinline__ void finish_group(const double (&s)[NT], const float 
 #pragma unroll
     for (int n = 0; n < NT; ++n) sum += exp((double)lg[n] - (double)sel0);   // exp(-inf) = 0 past E
   }
-#pragma unroll
-  for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+  sum += row_xor<8>(sum);
+  sum += row_xor<4>(sum);
+  sum += row_xor<2>(sum);
+  sum += row_xor<1>(sum);
   if (r < k && t < T) {
     topk_idx[(size_t)t * k + r] = myidx;
     if (s_idx != nullptr) s_idx[t * k + r] = myidx;   // a copy in LDS for what follows in the same kernel

@@ -161,23 +161,16 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
   if ((int)(threadIdx.x >> 6) < NS) {
     const int s = threadIdx.x >> 6;
     const SchedParams ps = pick(s);
-    int run = 0, rows_total = 0;
+    int run = 0;
     for (int g0 = 0; g0 < G; g0 += 64) {
       const int g = g0 + lane;
       const int rows = g < G ? s_rows[g] : 0;
       const int tiles = (rows + ps.BM - 1) / ps.BM;
-      int incl = tiles, rsum = rows;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int a = __shfl_up(incl, off);
-        if (lane >= off) incl += a;
-      }
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) rsum += __shfl_xor(rsum, off);
+      const int incl = wave_inclusive_scan(tiles);
       if (g < G) s_start[s][g] = run + incl - tiles;
-      run += __shfl(incl, 63);
-      rows_total += rsum;
+      run += __builtin_amdgcn_readlane(incl, 63);
     }
+    const int rows_total = s_row0[E - 1] + s_rows[E - 1] + S * T;   // all rows of all groups
     if (lane == 0) s_start[s][G] = run;
     const unsigned total = (unsigned)run * (unsigned)ps.n_ntiles;
     const unsigned per_xcd = (total + kXcds - 1) / kXcds;
@@ -201,21 +194,22 @@ __device__ __forceinline__ void build_schedules_block(const int32_t* local_offse
       const int sp = lane + 1;
       const int slots = ps.split_wgs / sp;
       float cost = INFINITY;
-      if (ps.split_kt > 0 && sp <= ps.split_max && slots >= 1 && ps.split_kt / sp >= ps.split_min_kt) {
+      if (ps.split_kt > 0 && sp <= min(ps.split_max, 8) && slots >= 1 && ps.split_kt / sp >= ps.split_min_kt) {
         const int rounds = ((int)per_xcd + slots - 1) / slots;   // per_xcd: the longest XCD list
         cost = (float)rounds * ((float)((ps.split_kt + sp - 1) / sp) + ps.split_round_kt) +
                (float)sp * (float)rows_total * ps.split_row_kt;
       }
+      static_assert(kDecodeSplits <= 8, "the candidates sit in lanes 0..7");
       int best = sp;
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) {
-        const float oc = __shfl_xor(cost, off);
-        const int ob = __shfl_xor(best, off);
+      auto meet = [&](float oc, int ob) {
         if (oc < cost || (oc == cost && ob < best)) {
           cost = oc;
           best = ob;
         }
-      }
+      };
+      meet(row_xor<4>(cost), row_xor<4>(best));
+      meet(row_xor<2>(cost), row_xor<2>(best));
+      meet(row_xor<1>(cost), row_xor<1>(best));
       if (lane == 0) ps.sched[2] = cost < INFINITY ? best : 1;
     }
   }
