@@ -109,12 +109,14 @@ __device__ __forceinline__ HistSums sum_block_hists(const int32_t* __restrict__ 
 // idx may have been written earlier in the same kernel by this workgroup (to memory with a
 // __syncthreads() in between, or to LDS with a barrier), hence no __restrict__ on it.
 // s_local_off (LDS, [E + 1], only without FROM_HIST): also receives the local offsets.
+// my_mask >= 0: thread e < E already holds mask[e] (read before the steps that precede the call,
+// so that its latency is not paid here).
 template <bool FROM_HIST>
 __device__ __forceinline__ void dispatch_place_block(
     const int32_t* idx, int A, int E, const uint8_t* __restrict__ mask,
     const int32_t* __restrict__ block_hist, int n_blocks, int sub, int block, const SplitOut& o,
     int32_t* __restrict__ local_src, int32_t* __restrict__ remote_src, int32_t* __restrict__ inv,
-    int* s_local_off = nullptr) {
+    int* s_local_off = nullptr, int my_mask = -1) {
   static_assert(PRISM_MAX_EXPERTS <= kThreads, "one thread per expert");
   // Only LDS data crosses between threads in here, so the barriers do not wait for
   // the global stores.
@@ -125,7 +127,11 @@ __device__ __forceinline__ void dispatch_place_block(
   __shared__ uint8_t s_mask[PRISM_MAX_EXPERTS];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  for (int e = threadIdx.x; e < E; e += kThreads) s_mask[e] = mask[e];
+  if (my_mask >= 0) {
+    if (threadIdx.x < E) s_mask[threadIdx.x] = (uint8_t)my_mask;
+  } else {
+    for (int e = threadIdx.x; e < E; e += kThreads) s_mask[e] = mask[e];
+  }
   if (FROM_HIST) {
     const HistSums hs = sum_block_hists(block_hist, n_blocks, E, block);
     if (threadIdx.x < E) s_total[threadIdx.x] = hs.total;

@@ -59,78 +59,126 @@ __device__ __forceinline__ void load_bias_group(const float* __restrict__ bias, 
   }
 }
 
-// From the complete fp64 logits of one token per 16-lane group (lane r of the group holds
-// experts 16 n + r of token t) to that token's top-k indices and gates.  Run by a whole
-// wavefront.  has_bias: add b (from load_bias_group) after the one rounding to fp32.
-// s_counts (LDS, may be NULL) receives +1 per selected expert.
+// From the complete fp64 logits of U tokens per 16-lane group (lane r of the group holds
+// experts 16 n + r of tokens t[0..U)) to those tokens' top-k indices and gates.  Run by a whole
+// wavefront.  The routing of a token is one long dependent chain (arg-max rounds, an fp64
+// exponential, a division); the U chains run side by side in one instruction stream.
+// has_bias: add b (from load_bias_group) after the one rounding to fp32.
+// s_counts (LDS, may be NULL) receives +1 per selected expert; s_idx (LDS, may be NULL) a copy
+// of topk_idx for what follows in the same kernel.
+template <int NT, int U>
+__device__ __forceinline__ void finish_groups(const double (&s)[U][NT], const float (&b)[U][NT],
+                                              bool has_bias, const int (&t)[U], int T, int E, int k,
+                                              int gate_mode, float* __restrict__ logits,
+                                              int32_t* topk_idx, float* __restrict__ topk_gate,
+                                              int* s_counts, int32_t* s_idx) {
+  const int r = threadIdx.x & 15;
+  // ---- one rounding to fp32, then the fp32 bias add --------------------------
+  float lg[U][NT];
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+      const int e = n * 16 + r;
+      float val = (float)s[u][n];
+      if (e < E && t[u] < T) {
+        if (has_bias) val = val + b[u][n];
+        if (logits != nullptr) logits[(size_t)t[u] * E + e] = val;
+      } else if (e >= E) {
+        val = -INFINITY;
+      }
+      lg[u][n] = val;
+    }
+
+  // ---- top-k: k rounds of arg-max over (logit, expert index) with xor-exchanges inside the
+  // group; equal logits resolve to the lower expert index.
+  float vals[U][NT];
+  float sel0[U], mysel[U];
+  int myidx[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int n = 0; n < NT; ++n) vals[u][n] = lg[u][n];
+    sel0[u] = 0.f; mysel[u] = 0.f; myidx[u] = 0;
+  }
+  for (int j = 0; j < k; ++j) {
+    float best[U];
+    int bidx[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      best[u] = vals[u][0];
+      bidx[u] = r;
+#pragma unroll
+      for (int n = 1; n < NT; ++n)
+        if (vals[u][n] > best[u]) { best[u] = vals[u][n]; bidx[u] = n * 16 + r; }
+    }
+    auto meet = [&](int u, float ov, int oi) {
+      if (ov > best[u] || (ov == best[u] && oi < bidx[u])) { best[u] = ov; bidx[u] = oi; }
+    };
+#pragma unroll
+    for (int u = 0; u < U; ++u) meet(u, row_xor<8>(best[u]), row_xor<8>(bidx[u]));
+#pragma unroll
+    for (int u = 0; u < U; ++u) meet(u, row_xor<4>(best[u]), row_xor<4>(bidx[u]));
+#pragma unroll
+    for (int u = 0; u < U; ++u) meet(u, row_xor<2>(best[u]), row_xor<2>(bidx[u]));
+#pragma unroll
+    for (int u = 0; u < U; ++u) meet(u, row_xor<1>(best[u]), row_xor<1>(bidx[u]));
+    // every lane of the group holds the winner; its owner retires it
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int n = 0; n < NT; ++n)
+        if (bidx[u] == n * 16 + r) vals[u][n] = -INFINITY;
+      if (j == 0) sel0[u] = best[u];
+      if (r == j) { mysel[u] = best[u]; myidx[u] = bidx[u]; }
+    }
+  }
+  // gates: softmax over the k picked logits, or the picked entries of the softmax over
+  // all experts; lane r < k owns slot r, sel0 is the token's largest logit
+  double w[U], sum[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    w[u] = r < k ? exp((double)mysel[u] - (double)sel0[u]) : 0.0;
+    sum[u] = w[u];
+  }
+  if (gate_mode == PRISM_GATES_SOFTMAX_ALL) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      sum[u] = 0.0;
+#pragma unroll
+      for (int n = 0; n < NT; ++n) sum[u] += exp((double)lg[u][n] - (double)sel0[u]);   // exp(-inf) = 0 past E
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    sum[u] += row_xor<8>(sum[u]);
+    sum[u] += row_xor<4>(sum[u]);
+    sum[u] += row_xor<2>(sum[u]);
+    sum[u] += row_xor<1>(sum[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (r < k && t[u] < T) {
+      topk_idx[(size_t)t[u] * k + r] = myidx[u];
+      if (s_idx != nullptr) s_idx[t[u] * k + r] = myidx[u];
+      topk_gate[(size_t)t[u] * k + r] = (float)(w[u] / sum[u]);
+      if (s_counts != nullptr) atomicAdd(&s_counts[myidx[u]], 1);
+    }
+}
+
 template <int NT>
 __device__ __forceinline__ void finish_group(const double (&s)[NT], const float (&b)[NT],
                                              bool has_bias, int t, int T, int E, int k, int gate_mode,
                                              float* __restrict__ logits, int32_t* topk_idx,
                                              float* __restrict__ topk_gate, int* s_counts,
                                              int32_t* s_idx = nullptr) {
-  const int r = threadIdx.x & 15;
-  // ---- one rounding to fp32, then the fp32 bias add --------------------------
-  float lg[NT];
+  double s1[1][NT];
+  float b1[1][NT];
 #pragma unroll
-  for (int n = 0; n < NT; ++n) {
-    const int e = n * 16 + r;
-    float val = (float)s[n];
-    if (e < E && t < T) {
-      if (has_bias) val = val + b[n];
-      if (logits != nullptr) logits[(size_t)t * E + e] = val;
-    } else if (e >= E) {
-      val = -INFINITY;
-    }
-    lg[n] = val;
-  }
-
-  // ---- top-k: k rounds of arg-max over (logit, expert index) with xor-exchanges inside the
-  // group; equal logits resolve to the lower expert index.
-  float vals[NT];
-#pragma unroll
-  for (int n = 0; n < NT; ++n) vals[n] = lg[n];
-  float sel0 = 0.f, mysel = 0.f;
-  int myidx = 0;
-  for (int j = 0; j < k; ++j) {
-    float best = vals[0];
-    int bidx = r;
-#pragma unroll
-    for (int n = 1; n < NT; ++n)
-      if (vals[n] > best) { best = vals[n]; bidx = n * 16 + r; }
-    auto meet = [&](float ov, int oi) {
-      if (ov > best || (ov == best && oi < bidx)) { best = ov; bidx = oi; }
-    };
-    meet(row_xor<8>(best), row_xor<8>(bidx));
-    meet(row_xor<4>(best), row_xor<4>(bidx));
-    meet(row_xor<2>(best), row_xor<2>(bidx));
-    meet(row_xor<1>(best), row_xor<1>(bidx));
-    // every lane of the group holds the winner; its owner retires it
-#pragma unroll
-    for (int n = 0; n < NT; ++n)
-      if (bidx == n * 16 + r) vals[n] = -INFINITY;
-    if (j == 0) sel0 = best;
-    if (r == j) { mysel = best; myidx = bidx; }
-  }
-  // gates: softmax over the k picked logits, or the picked entries of the softmax over
-  // all experts; lane r < k owns slot r, sel0 is the token's largest logit
-  double w = r < k ? exp((double)mysel - (double)sel0) : 0.0;
-  double sum = w;
-  if (gate_mode == PRISM_GATES_SOFTMAX_ALL) {
-    sum = 0.0;
-#pragma unroll
-    for (int n = 0; n < NT; ++n) sum += exp((double)lg[n] - (double)sel0);   // exp(-inf) = 0 past E
-  }
-  sum += row_xor<8>(sum);
-  sum += row_xor<4>(sum);
-  sum += row_xor<2>(sum);
-  sum += row_xor<1>(sum);
-  if (r < k && t < T) {
-    topk_idx[(size_t)t * k + r] = myidx;
-    if (s_idx != nullptr) s_idx[t * k + r] = myidx;   // a copy in LDS for what follows in the same kernel
-    topk_gate[(size_t)t * k + r] = (float)(w / sum);
-    if (s_counts != nullptr) atomicAdd(&s_counts[myidx], 1);
-  }
+  for (int n = 0; n < NT; ++n) { s1[0][n] = s[n]; b1[0][n] = b[n]; }
+  const int t1[1] = {t};
+  finish_groups<NT, 1>(s1, b1, has_bias, t1, T, E, k, gate_mode, logits, topk_idx, topk_gate, s_counts,
+                       s_idx);
 }
 
 // The same for a tile of 16 tokens held by one wavefront in the accumulator layout of
@@ -517,6 +565,8 @@ __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int n_tiles = (T + kTokPerBlock - 1) / kTokPerBlock;
+  // asked for now, used by the split: the load's latency passes during the routing
+  const int my_mask = (int)threadIdx.x < E ? (int)mask[threadIdx.x] : 0;
   __shared__ int32_t s_idx[kDispatchChunk];                 // topk_idx, for the split
   __shared__ int s_local_off[PRISM_MAX_EXPERTS + 1];        // local_offsets, for the schedules
   // A tile's routing is four units of four tokens (accumulator register v holds tokens
@@ -545,13 +595,24 @@ __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
       *reinterpret_cast<f64x4*>(s_sum + (size_t)tile * (NT * 256) + j * 4) = sum;
     }
     lds_barrier();
-    for (int tile = 0; tile < n_tiles; ++tile) {
-      f64x4 acc[NT];
+    // Wavefront w routes tokens 4w + q of every tile, two tiles per pass side by side.  The
+    // second tile of the last pass may not exist: its tokens are past T, so nothing is stored.
+    static_assert(kMaxTiles % 2 == 0, "tile pairs stay inside s_sum");
+    const int q = lane >> 4;
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+      double s2[2][NT];
+      float b2[2][NT];
+      int t2[2];
 #pragma unroll
-      for (int n = 0; n < NT; ++n)
-        acc[n] = *reinterpret_cast<const f64x4*>(s_sum + (size_t)tile * (NT * 256) + n * 256 + lane * 4);
-      finish_tile<NT>(acc, tile * kTokPerBlock, 1 << wave, bias, T, E, k, bias_group_tokens, gate_mode,
-                      nullptr, topk_idx, topk_gate, nullptr, s_idx);
+      for (int u = 0; u < 2; ++u) {
+        t2[u] = (tile + u) * kTokPerBlock + 4 * wave + q;
+#pragma unroll
+        for (int n = 0; n < NT; ++n)   // register v = wave of lane `lane` of the accumulator tile
+          s2[u][n] = s_sum[(size_t)(tile + u) * (NT * 256) + n * 256 + lane * 4 + wave];
+        load_bias_group<NT>(bias, t2[u], T, E, bias_group_tokens, b2[u]);
+      }
+      finish_groups<NT, 2>(s2, b2, bias != nullptr, t2, T, E, k, gate_mode, nullptr, topk_idx, topk_gate,
+                           nullptr, s_idx);
     }
   } else {
     // Too many expert columns for LDS: every wavefront sums the component it needs itself.
@@ -575,7 +636,7 @@ __global__ __launch_bounds__(kFrontThreads) void decode_front_end_kernel(
   }
   lds_barrier();   // s_idx is complete (the copy in memory is for the caller)
   dispatch_dev::dispatch_place_block<false>(s_idx, T * k, E, mask, nullptr, 1, 1, 0, o, local_src,
-                                            remote_src, inv, s_local_off);
+                                            remote_src, inv, s_local_off, my_mask);
   lds_barrier();   // s_local_off, written by the split
   const gg::SchedParams p[2] = {p0, p1};
   gg::build_schedules_block<2>(s_local_off, E, S, T, T * k, p);
