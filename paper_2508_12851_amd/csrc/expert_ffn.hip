@@ -320,19 +320,21 @@ auto select_path(const prism_layer_desc& d, int T, Fn&& fn) {
   // Batches of a few hundred tokens of a wide layer are still bound by streaming the weights
   // once, but an expert now has up to a few hundred rows; the down projection splits its
   // contraction as for decode batches.
-  // Up to 128 tokens an expert still has a single row tile of 128 (a token picks an expert at
-  // most once), so the weights are read once and stream.  128 x 128 tiles with 64-wide k-tiles
-  // there (4096 x 14336 layer, 5 of 8 experts hosted, 128 tokens: 0.388 ms against 0.418 with
-  // the tiles of the next case; at 256 tokens they lose, 0.471 against 0.466).
+  // Up to 256 tokens: 128 x 128 tiles with 64-wide k-tiles, weight loads non-temporal.  Up to
+  // 128 tokens an expert has a single row tile (a token picks an expert at most once), so the
+  // weights are read once and stream; between 129 and 256 the few experts with more than 128
+  // rows read theirs twice, which still beats the wider tiles of the next case (4096 x 14336
+  // layer, 5 of 8 experts hosted: 0.386 against 0.418 ms at 128 tokens, 0.381 against 0.413 at
+  // 129, 0.450 against 0.470 at 192, 0.470 against 0.480 at 256; at 320 they lose, 0.555 against
+  // 0.536).
   if (stream_tiles_apply(d, T) && T <= kMidMaxTokens)
     return fn(Path<TileCfg<128, 128, 64, 4>, TileCfg<128, 128, 64, 4>, true, true>{});
-  // Beyond, row tiles share weight tiles through the L2 and the non-temporal hint costs 8-13 %.
-  // Tiles twice as wide in weight rows (256) as in activation rows (128) bring twice the HBM
-  // bytes per k-tile for the same waits and barriers, and the padding rows of a half-empty
-  // 256-row tile would cost their loads and MFMAs like real ones.  (256 x 128 tiles: 0.50 ms
-  // for 256 tokens of the 4096 x 14336 layer with 5 of 8 experts hosted; 128 x 256: 0.43 ms;
-  // the 256 x 256 prefill tiles: 0.62 ms, their down projection has too few items to fill the
-  // machine.)
+  // Beyond, most experts have several row tiles, which share weight tiles through the L2 (the
+  // non-temporal hint costs 8-13 % there).  Tiles twice as wide in weight rows (256) as in
+  // activation rows (128) bring twice the HBM bytes per k-tile for the same waits and barriers,
+  // and the padding rows of a half-empty 256-row tile would cost their loads and MFMAs like
+  // real ones (256 x 128 tiles: 0.590 against 0.546 ms at 352 tokens; the 256 x 256 prefill
+  // tiles: their down projection has too few items to fill the machine).
   if (stream_tiles_apply(d, T))
     return fn(Path<TileCfg<128, 256, 32, 6>, TileCfg<128, 256, 32, 6>, true, false>{});
   // Prefill batch: 256 x 256 tiles (GEMM1: 128 gate + 128 up weight rows).  Very short

@@ -33,7 +33,7 @@ constexpr int kDispatchChunk = 2048;   // assignments per dispatch block
 constexpr int kDecodeMaxTokens = 64;    // batches up to this size take the weight-streaming path
 constexpr int kDecodeSplits = 8;        // most contraction slices of its down projection (the schedule builder picks how many)
 constexpr int kStreamMaxTokens = 512;   // wide bf16 layers: batches up to this size also split the down projection (expert_ffn.hip)
-constexpr int kMidMaxTokens = 128;      // ... and up to this size an expert still has one row tile of 128 (expert_ffn.hip)
+constexpr int kMidMaxTokens = 256;      // ... and up to this size they run in 128 x 128 tiles (expert_ffn.hip)
 constexpr int kMinTileM = 64;           // smallest row tile of the grouped GEMM (bounds table sizes)
 constexpr int kRouteTokTile = 16;       // tokens per router tile
 constexpr int kRouteMaxHSplit = 16;     // hidden-dimension slices of the decode router

@@ -97,11 +97,12 @@ def test_mixtral_decode_with_other_numbers_of_hosted_experts(n_local):
     _full_parity(cfg, inp, f"Mixtral decode, {n_local} hosted", layouts=("tiled",))
 
 
-@pytest.mark.parametrize("T", [96, 128, 200, 512, 1024, 1536, 2048])
+@pytest.mark.parametrize("T", [96, 128, 200, 300, 512, 1024, 1536, 2048])
 def test_mixtral_shape_other_batch_sizes_full_size(T):
     """The full Mixtral layer shape between the decode and the benchmark batch: 128 x 128 tiles
-    up to 128 tokens, 128 x 256 tiles up to 352, both with the split down projection; prefill
-    tiles whose last round of work items is only partly filled above."""
+    up to 256 tokens (one row tile per expert up to 128, two for the popular experts at 200),
+    128 x 256 tiles up to 352, both with the split down projection; prefill tiles whose last
+    round of work items is only partly filled above."""
     cfg = make_config("cfg2_mixtral_prefill", T=T)
     inp = make_inputs(cfg, weights="local", threads=16)
     _full_parity(cfg, inp, f"Mixtral shape, {T} tokens", layouts=("tiled",))
