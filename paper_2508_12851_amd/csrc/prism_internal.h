@@ -3,6 +3,7 @@
 #define PRISM_INTERNAL_H_
 
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -31,7 +32,9 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // ---------------------------------------------------------------------------
 constexpr int kDispatchChunk = 2048;   // assignments per dispatch block
 constexpr int kDecodeMaxTokens = 64;    // batches up to this size take the weight-streaming path
-constexpr int kDecodeSplits = 8;        // most contraction slices of its down projection (the schedule builder picks how many)
+constexpr int kDecodeSplits = 8;        // most contraction slices of its down projection (the schedule builder picks how many) ...
+constexpr int kStreamSplits = 4;        // ... and of batches with more than kManySplitsRows rows that still split it
+constexpr int kManySplitsRows = 256;    // (every slice is one more fp32 copy of all rows)
 constexpr int kStreamMaxTokens = 512;   // wide bf16 layers: batches up to this size also split the down projection (expert_ffn.hip)
 constexpr int kMidMaxTokens = 256;      // ... and up to this size they run in 128 x 128 tiles (expert_ffn.hip)
 constexpr int kMinTileM = 64;           // smallest row tile of the grouped GEMM (bounds table sizes)
@@ -46,7 +49,7 @@ struct Workspace {
   int32_t* tiles;          // 2 x [tile_table_ints]: schedules of the two grouped GEMMs
   void* h;                 // [(A + S*T) * F] layer dtype: silu(gate)*up
   void* y;                 // [(A + S*T) * H] layer dtype: expert outputs
-  float* part;             // batches up to kStreamMaxTokens: [kDecodeSplits][A + S*T][H] fp32 partial sums
+  float* part;             // batches up to kStreamMaxTokens: [max_splits(T)][A + S*T][H] fp32 partial sums
   float* slice_part;       // larger batches of wide layers: 256 partial tiles of 256 x 256 fp32 (cut last round of the down projection)
   double* route_part;      // decode batches: [token tiles][kRouteMaxHSplit][route_col_tiles][64][4] fp64
   size_t total;
@@ -95,6 +98,11 @@ static inline size_t slice_part_bytes(const prism_layer_desc& d, int T) {
   return down_slicing_applies(d, T) ? (size_t)256 * 256 * 256 * 4 : 0;
 }
 
+// Most contraction slices the down projection of a batch of T tokens may be split into.
+static inline int max_splits(const prism_layer_desc& d, int T) {
+  return (long long)T * (d.top_k + d.n_shared) <= kManySplitsRows ? kDecodeSplits : kStreamSplits;
+}
+
 static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
   Workspace w;
   const size_t A = (size_t)T * d.top_k;
@@ -118,7 +126,11 @@ static inline Workspace carve(const prism_layer_desc& d, int T, void* base) {
   const size_t t_str = (size_t)(T < kStreamMaxTokens ? T : kStreamMaxTokens);
   const size_t rows_str = t_str * (size_t)(d.top_k + d.n_shared);
   const bool bf16 = d.dtype == PRISM_BF16;
-  w.part = (float*)take(bf16 ? (size_t)kDecodeSplits * rows_str * d.hidden * 4 : 0);
+  // up to kManySplitsRows rows the down projection may be split into kDecodeSplits slices,
+  // beyond into kStreamSplits: the larger of the two needs (max_splits)
+  const size_t planes_rows = std::max((size_t)kDecodeSplits * std::min(rows_str, (size_t)kManySplitsRows),
+                                      (size_t)kStreamSplits * rows_str);
+  w.part = (float*)take(bf16 ? planes_rows * d.hidden * 4 : 0);
   w.slice_part = (float*)take(slice_part_bytes(d, T));
   w.route_part = (double*)take(bf16 ? (size_t)ceil_div((int)t_dec, kRouteTokTile) * kRouteMaxHSplit *
                                           route_col_tiles(d.n_experts) * 64 * 4 * 8 : 0);

@@ -312,7 +312,7 @@ static inline void ffn_sched_params(const prism_layer_desc& d, int T, int32_t* t
   *p0 = SchedParams{f.bm1, f.nt1, sched_capacity(d, T, f.bm1, f.nt1), tiles, f.interleave ? 1 : 0,
                     0, 0, 0, 0, 0, 0.f, 0.f};
   *p1 = SchedParams{f.bm2, f.nt2, sched_capacity(d, T, f.bm2, f.nt2), tiles + tile_table_ints(d, T),
-                    f.interleave ? 1 : 0, f.slice_kt2, f.split_kt2, kDecodeSplits, f.split_min_kt2,
+                    f.interleave ? 1 : 0, f.slice_kt2, f.split_kt2, max_splits(d, T), f.split_min_kt2,
                     f.split_wgs2, f.split_round_kt2, f.split_row_kt2};
 }
 
