@@ -110,13 +110,17 @@ def cpu_baseline(inp, n_sample: int):
     f = inp.f32
     n = min(n_sample, c.T)
     xs = f(inp.x)[:n]
-    t0 = time.perf_counter()
-    O.moe_layer(xs, f(inp.w_router), inp.bias, lambda e: tuple(f(w) for w in inp.expert(e)),
-                [tuple(f(w) for w in inp.shared(s)) for s in range(c.S)], inp.mask, c.k, c.dtype,
-                c.bias_group_tokens, np.arange(n))
-    dt = time.perf_counter() - t0
-    return {"value": n / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"first {n} of {c.T} tokens of {c.name}, whole layer, {dt:.1f} s"}
+    # whole passes over the sample until about 10 s of CPU work are on the clock (4 passes at most)
+    passes, dt = 0, 0.0
+    while passes < 4 and dt < 10.0:
+        t0 = time.perf_counter()
+        O.moe_layer(xs, f(inp.w_router), inp.bias, lambda e: tuple(f(w) for w in inp.expert(e)),
+                    [tuple(f(w) for w in inp.shared(s)) for s in range(c.S)], inp.mask, c.k, c.dtype,
+                    c.bias_group_tokens, np.arange(n))
+        dt += time.perf_counter() - t0
+        passes += 1
+    return {"value": n * passes / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n} of {c.T} tokens of {c.name}, whole layer, {passes} passes, {dt:.1f} s"}
 
 
 class DeviceWeights:
