@@ -1,6 +1,9 @@
 """Build libprism.so (HIP kernels + C ABI) for gfx950, in-tree.
 
-    python -m paper_2508_12851_amd.build
+    python -m paper_2508_12851_amd.build [--define NAME=VALUE ...]
+
+--define passes -DNAME=VALUE to every compilation: for measurements that vary a compile-time
+constant of the kernels (a plain rebuild afterwards restores the library everything else uses).
 
 Each .hip file under csrc/ is compiled to an object in _build/ (in parallel),
 then linked into paper_2508_12851_amd/libprism.so.
@@ -40,14 +43,15 @@ def sources():
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
-def build_library(verbose: bool = True, jobs: int = 8) -> str:
+def build_library(verbose: bool = True, jobs: int = 8, defines=()) -> str:
     os.makedirs(BUILD, exist_ok=True)
     srcs = sources()
+    flags = FLAGS + ["-D" + d for d in defines]
     objs = [os.path.join(BUILD, os.path.basename(s)[:-4] + ".o") for s in srcs]
 
     def compile_one(pair):
         s, o = pair
-        out = _run([HIPCC, *FLAGS, "-c", s, "-o", o])
+        out = _run([HIPCC, *flags, "-c", s, "-o", o])
         return s, out
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
@@ -63,5 +67,8 @@ def build_library(verbose: bool = True, jobs: int = 8) -> str:
 
 
 if __name__ == "__main__":
-    build_library()
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--define", action="append", default=[], metavar="NAME=VALUE")
+    build_library(defines=ap.parse_args().define)
     sys.exit(0)

@@ -66,7 +66,10 @@ constexpr int kReduceInts = 8;       // ints per entry of the list of sliced ite
 // same length to within one item.
 // The number of items (row tiles x column tiles) must stay below 2^31, which the int
 // capacity of a list already implies.
-constexpr int kRectRows = 8;
+#ifndef PRISM_RECT_ROWS
+#define PRISM_RECT_ROWS 8   // other values: for measurements of the work order (build.py --define)
+#endif
+constexpr int kRectRows = PRISM_RECT_ROWS;
 
 struct SchedParams {
   int BM;            // row tile
