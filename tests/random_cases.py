@@ -59,3 +59,23 @@ def draw_wide_case(i):
     return dict(dtype="bf16", T=T, H=H, F=F, E=E, k=k, S=S, n_local=n_local, n_swapped=0,
                 bias_group_tokens=pick([0, 0, 256]), mask_kind=pick(["top", "random"]),
                 zipf_s=pick([0.0, 1.0]), seed=300 + i), bool(rng.integers(0, 2))
+
+
+def draw_streaming_case(i):
+    """Random batches of up to 352 tokens of layers wide enough for the paths that stream the
+    weights once (H >= 256, F >= 1024): decode tiles up to 64 tokens, 128 x 128 tiles up to 256,
+    128 x 256 tiles beyond, each with the down projection split into a number of slices that the
+    schedule builder picks from the number of experts that received tokens -- which the expert
+    count, the mask and the popularity skew vary from case to case."""
+    rng = np.random.default_rng(12000 + i)
+    pick = lambda seq: seq[int(rng.integers(0, len(seq)))]
+    E = pick([2, 4, 8, 8, 16, 32])
+    k = int(rng.integers(1, min(4, E) + 1))
+    S = pick([0, 0, 1])
+    H, F = pick([256, 512, 1024, 2048]), pick([1024, 1536, 2048, 4096])
+    T = int(pick([rng.integers(1, 65), rng.integers(65, 257), rng.integers(257, 353)]))
+    n_local = int(pick([E, max(1, E - 1), int(rng.integers(1, E + 1))]))
+    return dict(dtype="bf16", T=T, H=H, F=F, E=E, k=k, S=S, n_local=n_local, n_swapped=0,
+                bias_group_tokens=pick([0, 0, 32]), mask_kind=pick(["top", "random"]),
+                zipf_s=pick([0.0, 1.0, 2.0]), seed=500 + i), bool(rng.integers(0, 2))
+

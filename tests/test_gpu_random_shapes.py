@@ -118,3 +118,20 @@ def test_layer_parity_on_a_random_wide_shape(i):
     o = run_layer(cfg, inp, wt=weight_table(inp, tiled=tiled), weight_layout="tiled" if tiled else "row_major")
     err = check_layer(cfg, o, ref)
     print(f"wide case {i}: out err {err:.3g}, n_local {ref.dispatch.n_local}, n_remote {ref.dispatch.n_remote}")
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_layer_parity_on_a_random_streaming_shape(i):
+    """Batches of 1 to 352 tokens of wide layers, where the expert FFN streams the weights once and
+    splits the down projection's contraction by a count chosen on the device: whole layer against
+    the oracle, whole-batch error measure."""
+    from random_cases import draw_streaming_case
+    kw, tiled = draw_streaming_case(i)
+    print(f"streaming case {i}: {kw} tiled={tiled}", flush=True)
+    cfg = make_config("cfg3_mixtral_decode", **kw)
+    inp = make_inputs(cfg)
+    ref = oracle_layer(inp)
+    o = run_layer(cfg, inp, wt=weight_table(inp, tiled=tiled), weight_layout="tiled" if tiled else "row_major")
+    err = check_layer(cfg, o, ref)
+    print(f"streaming case {i}: out err {err:.3g}, n_local {ref.dispatch.n_local}, n_remote {ref.dispatch.n_remote}")
+
