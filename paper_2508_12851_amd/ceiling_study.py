@@ -1,6 +1,11 @@
 """What is the fastest this GPU streams from HBM, and with which access pattern?
 
     python -m paper_2508_12851_amd.ceiling_study [--gib 4] [--reps 3]
+    python -m paper_2508_12851_amd.ceiling_study --single-launch-mib 1120
+
+The second form times ONE launch that reads the given number of MiB (the weights one decode
+GEMM streams), start-up and tail of the launch included, on buffers that rotate so that no
+launch finds its data in the last-level cache: what a kernel of that size can reach at best.
 
 Sweeps prism_ceiling_hbm_read_pattern over workgroups per launch, loads in flight per thread,
 contiguous span per workgroup and load kind, on a zero-filled buffer 16x the last-level cache,
@@ -18,12 +23,34 @@ import paper_2508_12851_amd as P
 MODES = {0: "registers", 1: "direct-to-LDS", 2: "non-temporal", 3: "LDS non-temporal"}
 
 
+def single_launch(nbytes):
+    import numpy as np
+    bufs = [torch.zeros(nbytes, dtype=torch.uint8, device="cuda") for _ in range(4)]
+    sink = torch.empty(65536 * 4096, dtype=torch.uint8, device="cuda")
+    print(f"one launch reading {nbytes / 1e6:.0f} MB, median of 10 launches on 4 rotating buffers")
+    for grid, mode, u, span in itertools.product((224, 256), (1, 3, 2), (8, 16), (256 << 10, 512 << 10, 1 << 20)):
+        ts = []
+        for i in range(12):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            n = P.prism_ceiling_hbm_read_pattern(bufs[i % 4], sink, grid, u, span, mode)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        t = float(np.median(ts[2:]))
+        print(f"{MODES[mode]:<16} workgroups {grid}  in flight {u:>2}  span {span >> 10:>5} KiB: {t * 1e3:7.1f} us  "
+              f"{n / t / 1e6:7.1f} GB/s", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gib", type=int, default=4)
     ap.add_argument("--reps", type=int, default=3)
     ap.add_argument("--json", default=None, help="also write all points to this file")
+    ap.add_argument("--single-launch-mib", type=int, default=None)
     args = ap.parse_args()
+    if args.single_launch_mib is not None:
+        return single_launch(args.single_launch_mib << 20)
     nbytes = args.gib << 30
     src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
     sink = torch.empty(65536 * 4096, dtype=torch.uint8, device="cuda")
