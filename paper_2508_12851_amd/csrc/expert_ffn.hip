@@ -178,31 +178,49 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restr
 
 // Adds up the slices of the down-projection tiles whose contraction the schedule cut (its last
 // round of work items): y tile = bf16(sum of the tile's fp32 partial tiles, in slice order).
-// One workgroup per (line of the schedule's list of sliced items, 32 rows of the tile); lines
-// that are not in use end at once.
+// One workgroup per (line of the schedule's list of sliced items, 16 rows of the tile) -- few
+// lines are in use at a time, so the rows of a tile are spread over many workgroups; lines that
+// are not in use end at once.
 constexpr int kSliceTile = 256;    // the partial tiles are 256 x 256 (the prefill tile)
+constexpr int kSumRows = 16;       // rows of a tile per workgroup of sum_slices_kernel
+constexpr int kSumChunks = kSliceTile / kSumRows;
 __global__ __launch_bounds__(256) void sum_slices_kernel(const int32_t* __restrict__ sched, int capacity,
                                                          const float* __restrict__ part, int N,
                                                          uint16_t* __restrict__ y) {
-  const int line = blockIdx.x / 8, chunk = blockIdx.x % 8;
+  const int line = blockIdx.x / kSumChunks, chunk = blockIdx.x % kSumChunks;
   const int4* red = reinterpret_cast<const int4*>(sched + gg::sched_reduce_offset(capacity)) +
                     (size_t)line * (gg::kReduceInts / 4);
   const int n_slices = red[1].x;
   if (n_slices <= 0) return;
   const int4 a = red[0];
   const int row_start = a.x, row_count = a.y, first = a.w;
-  const int row_end = min(row_count, chunk * 32 + 32);
+  const int row_end = min(row_count, chunk * kSumRows + kSumRows);
   const int col0 = a.z * kSliceTile;
   const int col = (threadIdx.x & 63) * 4;
   if (col0 + col >= N) return;
-  for (int r = chunk * 32 + (threadIdx.x >> 6); r < row_end; r += 4) {
-    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < n_slices; ++c)
-      sum += *reinterpret_cast<const f32x4*>(part + ((size_t)(first + c) * kSliceTile + r) * kSliceTile + col);
-    bf16x4 o;
+  // Two rows per wavefront and pass; all slices of both rows are asked for before the first is
+  // added (the partial tiles are read once: non-temporal); the sums themselves run in slice order.
+  for (int r0 = chunk * kSumRows + (threadIdx.x >> 6); r0 < row_end; r0 += 8) {
+    f32x4 v[2][gg::kMaxSlices];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)sum[e];
-    *reinterpret_cast<bf16x4*>(y + (size_t)(row_start + r) * N + col0 + col) = o;
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int c = 0; c < gg::kMaxSlices; ++c)
+        if (c < n_slices && r0 + 4 * u < row_end)
+          v[u][c] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(
+              part + ((size_t)(first + c) * kSliceTile + r0 + 4 * u) * kSliceTile + col));
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      if (r0 + 4 * u >= row_end) break;
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < gg::kMaxSlices; ++c)
+        if (c < n_slices) sum += v[u][c];
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16_t)sum[e];
+      *reinterpret_cast<bf16x4*>(y + (size_t)(row_start + r0 + 4 * u) * N + col0 + col) = o;
+    }
   }
 }
 
@@ -272,7 +290,7 @@ prism_status run_bf16_ffn(const prism_layer_desc& d, const void* x, const prism_
           g2, gg::sched_capacity(d, T, C2::BM, nt2), st)));
   }
   if (slice_kt > 0) {
-    hipLaunchKernelGGL(sum_slices_kernel, dim3(gg::kXcds * (gg::kSliceSlots / 2) * 8), dim3(256), 0, st, sched2,
+    hipLaunchKernelGGL(sum_slices_kernel, dim3(gg::kXcds * (gg::kSliceSlots / 2) * kSumChunks), dim3(256), 0, st, sched2,
                        gg::sched_capacity(d, T, C2::BM, nt2), slice_part, d.hidden, (uint16_t*)y);
     PRISM_CHECK_LAUNCH();
   }
