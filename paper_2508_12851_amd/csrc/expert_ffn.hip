@@ -160,16 +160,21 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restr
                                                             int E, int A, int rows, int H,
                                                             const int32_t* __restrict__ n_splits_ptr,
                                                             uint16_t* __restrict__ y) {
-  const int n_splits = *n_splits_ptr;   // what the schedule builder chose
+  const int n_splits = min(*n_splits_ptr, kDecodeSplits);   // what the schedule builder chose
   const int vec_per_row = H / 4;
   const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= (long long)rows * vec_per_row) return;
   const int row = (int)(gid / vec_per_row);
   if (row >= local_offsets[E] && row < A) return;   // rows that hold no assignment
   const int col = (int)(gid - (long long)row * vec_per_row) * 4;
+  f32x4 v[kDecodeSplits];   // all slices asked for before the first is added
+#pragma unroll
+  for (int s = 0; s < kDecodeSplits; ++s)
+    if (s < n_splits) v[s] = *reinterpret_cast<const f32x4*>(part + ((size_t)s * rows + row) * H + col);
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < n_splits; ++s)
-    acc += *reinterpret_cast<const f32x4*>(part + ((size_t)s * rows + row) * H + col);
+#pragma unroll
+  for (int s = 0; s < kDecodeSplits; ++s)
+    if (s < n_splits) acc += v[s];
   bf16x4 o;
 #pragma unroll
   for (int e = 0; e < 4; ++e) o[e] = (bf16_t)acc[e];
