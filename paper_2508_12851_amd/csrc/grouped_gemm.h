@@ -400,8 +400,12 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_gemm_kernel(const GemmAr
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+        for (int j0 = 0; j0 < NJ; ++j0) {
+          // snake order over the grid of accumulators: every MFMA shares an operand with the one
+          // before it (0.5 % on the power-limited prefill GEMMs)
+          const int j = (i & 1) ? NJ - 1 - j0 : j0;
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+        }
       // Issue order inside the step: one MFMA first (so the wait for this step's
       // operands precedes any new LDS read), then the next step's operand reads one
       // per MFMA, then this step's share of the refill one per MFMA.
